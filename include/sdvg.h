@@ -1,0 +1,151 @@
+/*
+ * sdvg.h -- C ABI of libsdvg: block-causal attention over a KV cache, KV-cache commit and
+ * rollback, and worst-frame routing, for speculative decoding of autoregressive video
+ * generation (SDVG) on AMD MI355X (gfx950).
+ *
+ * Conventions shared by every call
+ *   - Pointers named "device" are HIP device pointers owned by the caller; the library never
+ *     frees or reallocates them. Pointers named "host" are ordinary host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every call returns an int: >= 0 on success, a negative sdvg_status on error. Arguments
+ *     are validated on the host before anything is launched; on error nothing is launched
+ *     and no state (device memory, descriptor fields) is changed. No call throws or aborts.
+ *   - Strides are in elements of the tensor's type; the innermost (dim) stride is always 1.
+ *   - Logical index order is (layer, token, head, dim). head_dim must be 128.
+ *   - bf16 tensors are raw bfloat16 bit patterns (2 bytes per element).
+ */
+#ifndef SDVG_H
+#define SDVG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SDVG_OK = 0,
+  SDVG_ERR_NULL = -1,        /* a required pointer is NULL */
+  SDVG_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent */
+  SDVG_ERR_RANGE = -3,       /* slot / length / threshold outside its valid range */
+  SDVG_ERR_ALIGN = -4,       /* pointer not 16-byte aligned, or stride not a multiple of 8 */
+  SDVG_ERR_UNSUPPORTED = -5, /* head_dim != 128, unknown dtype or mode */
+  SDVG_ERR_DEVICE = -6       /* a HIP runtime call failed (see sdvg_last_device_error) */
+} sdvg_status;
+
+enum { SDVG_BF16 = 0, SDVG_F32 = 1 };
+
+/*
+ * Describes the caller-owned KV cache of one model: two device arrays k and v of bf16,
+ * logical [n_layers][capacity_tokens][n_heads][head_dim]. cache_len is a HOST field: the
+ * number of valid tokens (the same in every layer); commit and rollback update it at enqueue
+ * time, so later calls on the same stream see a consistent length.
+ */
+typedef struct {
+  void *k, *v;              /* device */
+  int32_t n_layers, n_heads, head_dim;
+  int32_t block_tokens;     /* T: tokens per video block (3 latent frames) */
+  int64_t capacity_tokens;  /* tokens allocated per layer */
+  int64_t cache_len;        /* valid tokens, 0 <= cache_len <= capacity_tokens */
+  int64_t layer_stride, token_stride, head_stride; /* elements */
+} sdvg_kv_cache;
+
+/* Shapes and strides of one attention call (one layer, one denoising step). */
+typedef struct {
+  int32_t n_q;      /* query tokens of the current block */
+  int32_t n_blk;    /* key/value tokens of the current block (normally == n_q) */
+  int32_t n_heads;
+  int32_t head_dim; /* must be 128 */
+  int64_t q_token_stride, q_head_stride;     /* q */
+  int64_t o_token_stride, o_head_stride;     /* out */
+  int64_t kv_token_stride, kv_head_stride;   /* k_cache, v_cache (one layer) */
+  int64_t blk_token_stride, blk_head_stride; /* k_blk, v_blk */
+  float scale;      /* softmax scale, 1/sqrt(head_dim) in the paper's models */
+  int32_t dtype;    /* SDVG_BF16: all tensors bf16. SDVG_F32: all tensors fp32 (check path) */
+} sdvg_attn_desc;
+
+/*
+ * Block-causal attention of one video block over the KV cache (paper Sec. 1: blocks are
+ * generated against a shared KV cache; Sec. 4.1 "Models": causal attention backbone with KV
+ * caching). For every head h and query row i:
+ *     out[i,h,:] = sum_j p_ij V[j,h,:],   p_i = softmax_j(scale * q[i,h,:] . K[j,h,:]),
+ * where K, V are the cache's first cache_len tokens followed by the block's n_blk tokens.
+ * No mask: a block's queries see the whole cache and the whole block.
+ *   desc      host. Shapes, strides, scale, dtype.
+ *   q         device [n_q][n_heads][128]; k_blk, v_blk device [n_blk][n_heads][128].
+ *   k_cache, v_cache  device, ONE layer's base pointers, at least cache_len tokens; may be
+ *             NULL when cache_len == 0. Tokens at or past cache_len are never read.
+ *   out       device [n_q][n_heads][128], same dtype as the inputs; every element is written.
+ *   Arithmetic (bf16): products on the matrix cores with fp32 accumulation, fp32 softmax
+ *   statistics, probabilities rounded to bf16 before the PV product, bf16 output (RNE).
+ * Asynchronous: enqueued on `stream`; returns SDVG_OK or a negative status.
+ */
+int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cache,
+                    const void *v_cache, const void *k_blk, const void *v_blk,
+                    int64_t cache_len, void *out, void *stream);
+
+/*
+ * KV commit (paper Sec. 3 "Inference flow": an accepted draft block is committed to the
+ * target's KV cache; a regenerated block updates it; the drafter's own cache is updated
+ * unconditionally). Copies k_blk, v_blk -- device, dense [n_layers][T][n_heads][128] bf16 --
+ * into tokens [slot*T, (slot+1)*T) of every layer, then sets cache->cache_len = (slot+1)*T.
+ * Append-only: requires slot*T == cache->cache_len and (slot+1)*T <= capacity_tokens, else
+ * SDVG_ERR_RANGE. One launch covers all layers. Asynchronous on `stream`.
+ */
+int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk, int32_t slot,
+                   void *stream);
+
+/*
+ * KV rollback (paper Sec. 3 "Inference flow", reject branch: the target regenerates the block
+ * as if the draft had never been in its cache). Sets cache->cache_len = new_len and zero-fills
+ * tokens [new_len, old cache_len) of k and v in every layer, so no rejected data survives.
+ * Requires 0 <= new_len <= cache->cache_len, else SDVG_ERR_RANGE; equal lengths is a no-op.
+ * Asynchronous on `stream`.
+ */
+int sdvg_kv_rollback(sdvg_kv_cache *cache, int64_t new_len, void *stream);
+
+/*
+ * Worst-frame routing (paper Sec. 3 Eq. (1): q_b = min over the block's F decoded frames of
+ * the per-frame reward; "Inference flow": accept iff q_b >= tau; "Force-reject the first
+ * block": block 0 is always rejected, whatever its score).
+ *   frame_scores  device, n_frames fp32 rewards (n_frames >= 1).
+ *   tau           threshold; NaN -> SDVG_ERR_RANGE.
+ *   block_idx     >= 0.
+ *   q_b_out       host, nullable: receives q_b (also for block 0).
+ * Any NaN score -> reject with q_b = quiet NaN (bits 0x7FC00000). Of +0.0 and -0.0 the
+ * negative zero is the smaller, so q_b is bit-exact under any reduction order.
+ * Synchronises `stream` (the caller branches on the result, as the paper's loop does).
+ * Returns 1 (accept), 0 (reject) or a negative status.
+ */
+int sdvg_worst_frame_route(const float *frame_scores, int32_t n_frames, float tau,
+                           int32_t block_idx, float *q_b_out, void *stream);
+
+/*
+ * Batched, asynchronous form of the same rule for n_blocks blocks at once.
+ *   frame_scores  device [n_blocks][n_frames] fp32, dense.
+ *   block_idx     device, n_blocks int32 (the block's position in its video), or NULL
+ *                 meaning block i has index first_block_idx + i.
+ *   decisions_out device, n_blocks int32 (1 accept / 0 reject); q_b_out device, n_blocks
+ *                 fp32, nullable.
+ * Does not synchronise. Returns SDVG_OK or a negative status.
+ */
+int sdvg_worst_frame_route_batch(const float *frame_scores, int32_t n_blocks, int32_t n_frames,
+                                 float tau, const int32_t *block_idx, int32_t first_block_idx,
+                                 int32_t *decisions_out, float *q_b_out, void *stream);
+
+/* Human-readable name of a status code (static storage; never NULL). */
+const char *sdvg_status_string(int status);
+
+/* hipError_t of the most recent SDVG_ERR_DEVICE on this thread, as an int (0 if none). */
+int sdvg_last_device_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int sdvg_version(void);
+
+/* Releases the small pinned host buffer the router keeps. Safe to call more than once. */
+void sdvg_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDVG_H */

@@ -1,0 +1,199 @@
+"""ctypes binding of libsdvg.so. Argument marshalling only: same names as the C entry points.
+
+PyTorch tensors supply device memory (`data_ptr()`) and the HIP stream; nothing is computed
+here and there is no fallback: a missing library raises.
+"""
+import ctypes
+import math
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsdvg.so")
+
+SDVG_BF16, SDVG_F32 = 0, 1
+
+
+class SdvgError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s failed: %s" % (where, status_string(status)))
+
+
+class sdvg_kv_cache(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("n_layers", ctypes.c_int32), ("n_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("block_tokens", ctypes.c_int32),
+                ("capacity_tokens", ctypes.c_int64), ("cache_len", ctypes.c_int64),
+                ("layer_stride", ctypes.c_int64), ("token_stride", ctypes.c_int64),
+                ("head_stride", ctypes.c_int64)]
+
+
+class sdvg_attn_desc(ctypes.Structure):
+    _fields_ = [("n_q", ctypes.c_int32), ("n_blk", ctypes.c_int32),
+                ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("q_token_stride", ctypes.c_int64), ("q_head_stride", ctypes.c_int64),
+                ("o_token_stride", ctypes.c_int64), ("o_head_stride", ctypes.c_int64),
+                ("kv_token_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64),
+                ("blk_token_stride", ctypes.c_int64), ("blk_head_stride", ctypes.c_int64),
+                ("scale", ctypes.c_float), ("dtype", ctypes.c_int32)]
+
+
+_LIB = None
+
+
+def lib():
+    """The loaded libsdvg.so; raises if it was never built."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libsdvg.so is missing: build it with `python -m paper_2604_17397_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+        L.sdvg_block_attn.restype = ctypes.c_int
+        L.sdvg_block_attn.argtypes = [ctypes.POINTER(sdvg_attn_desc), vp, vp, vp, vp, vp, i64, vp, vp]
+        L.sdvg_kv_commit.restype = ctypes.c_int
+        L.sdvg_kv_commit.argtypes = [ctypes.POINTER(sdvg_kv_cache), vp, vp, i32, vp]
+        L.sdvg_kv_rollback.restype = ctypes.c_int
+        L.sdvg_kv_rollback.argtypes = [ctypes.POINTER(sdvg_kv_cache), i64, vp]
+        L.sdvg_worst_frame_route.restype = ctypes.c_int
+        L.sdvg_worst_frame_route.argtypes = [vp, i32, f32, i32, ctypes.POINTER(f32), vp]
+        L.sdvg_worst_frame_route_batch.restype = ctypes.c_int
+        L.sdvg_worst_frame_route_batch.argtypes = [vp, i32, i32, f32, vp, i32, vp, vp, vp]
+        L.sdvg_status_string.restype = ctypes.c_char_p
+        L.sdvg_status_string.argtypes = [ctypes.c_int]
+        L.sdvg_last_device_error.restype = ctypes.c_int
+        L.sdvg_version.restype = ctypes.c_int
+        L.sdvg_shutdown.restype = None
+        _LIB = L
+    return _LIB
+
+
+def status_string(status):
+    return lib().sdvg_status_string(int(status)).decode()
+
+
+def _stream_ptr(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _check_dev(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("libsdvg takes device tensors")
+
+
+class KVCache:
+    """Caller-owned KV cache of one model: k, v are bf16 device tensors whose logical view is
+    [layers, capacity_tokens, heads, 128] (any layer/token/head strides, unit dim stride)."""
+
+    def __init__(self, k, v, block_tokens, cache_len=0):
+        _check_dev(k, v)
+        assert k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
+        assert k.dim() == 4 and k.shape == v.shape and k.stride() == v.stride() and k.stride(3) == 1
+        self.k, self.v = k, v
+        self.c = sdvg_kv_cache(k.data_ptr(), v.data_ptr(), k.shape[0], k.shape[2], k.shape[3],
+                               int(block_tokens), k.shape[1], int(cache_len),
+                               k.stride(0), k.stride(1), k.stride(2))
+
+    @property
+    def cache_len(self):
+        return int(self.c.cache_len)
+
+    def layer(self, i):
+        """(k, v) views [capacity, heads, 128] of layer i."""
+        return self.k[i], self.v[i]
+
+
+def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=None, stream=None):
+    """sdvg_block_attn: q, k_blk, v_blk [tokens, heads, 128]; k_cache, v_cache one layer's
+    [>= cache_len, heads, 128] (may be None when cache_len == 0). Returns out."""
+    _check_dev(q, k_cache, v_cache, k_blk, v_blk, out)
+    if q.dtype == torch.bfloat16:
+        dtype = SDVG_BF16
+    elif q.dtype == torch.float32:
+        dtype = SDVG_F32
+    else:
+        raise TypeError("q must be bfloat16 or float32")
+    for t in (k_cache, v_cache, k_blk, v_blk):
+        if t is not None and (t.dtype != q.dtype or t.dim() != 3 or t.stride(2) != 1):
+            raise ValueError("all tensors share q's dtype, are 3-d and have unit dim stride")
+    if out is None:
+        out = torch.empty(q.shape, dtype=q.dtype, device=q.device)
+    if k_blk.stride() != v_blk.stride() or (k_cache is not None and k_cache.stride() != v_cache.stride()):
+        raise ValueError("k and v must share strides")
+    kv_ts, kv_hs = (k_cache.stride(0), k_cache.stride(1)) if k_cache is not None else (128, 128)
+    d = sdvg_attn_desc(q.shape[0], k_blk.shape[0], q.shape[1], q.shape[2],
+                       q.stride(0), q.stride(1), out.stride(0), out.stride(1),
+                       kv_ts, kv_hs, k_blk.stride(0), k_blk.stride(1),
+                       (1.0 / math.sqrt(q.shape[2])) if scale is None else float(scale), dtype)
+    st = lib().sdvg_block_attn(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_blk),
+                               _ptr(v_blk), int(cache_len), _ptr(out), _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_block_attn")
+    return out
+
+
+def kv_commit(cache, k_blk, v_blk, slot, stream=None):
+    """sdvg_kv_commit: k_blk, v_blk dense bf16 [layers, T, heads, 128]."""
+    _check_dev(k_blk, v_blk)
+    if not (k_blk.is_contiguous() and v_blk.is_contiguous()):
+        raise ValueError("k_blk and v_blk must be dense")
+    L, T, H, D = cache.c.n_layers, cache.c.block_tokens, cache.c.n_heads, cache.c.head_dim
+    if tuple(k_blk.shape) != (L, T, H, D) or tuple(v_blk.shape) != (L, T, H, D):
+        raise ValueError("block shape must be [layers, T, heads, dim] of the cache")
+    if k_blk.dtype != torch.bfloat16 or v_blk.dtype != torch.bfloat16:
+        raise TypeError("k_blk and v_blk must be bfloat16")
+    st = lib().sdvg_kv_commit(ctypes.byref(cache.c), _ptr(k_blk), _ptr(v_blk), int(slot),
+                              _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_kv_commit")
+
+
+def kv_rollback(cache, new_len, stream=None):
+    st = lib().sdvg_kv_rollback(ctypes.byref(cache.c), int(new_len), _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_kv_rollback")
+
+
+def worst_frame_route(frame_scores, tau, block_idx, stream=None):
+    """sdvg_worst_frame_route: returns (decision, q_b) with q_b a numpy float32 scalar."""
+    import numpy as np
+    _check_dev(frame_scores)
+    if frame_scores.dtype != torch.float32 or frame_scores.dim() != 1 or not frame_scores.is_contiguous():
+        raise ValueError("frame_scores must be a dense 1-d float32 tensor")
+    qb = np.zeros(1, dtype=np.float32)
+    st = lib().sdvg_worst_frame_route(_ptr(frame_scores), frame_scores.numel(), float(tau),
+                                      int(block_idx),
+                                      qb.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                      _stream_ptr(stream))
+    if st < 0:
+        raise SdvgError(st, "sdvg_worst_frame_route")
+    return int(st), qb[0]
+
+
+def worst_frame_route_batch(frame_scores, tau, block_idx=None, first_block_idx=0, stream=None):
+    """sdvg_worst_frame_route_batch: frame_scores [n_blocks, n_frames] fp32; returns device
+    tensors (decisions int32 [n_blocks], q_b float32 [n_blocks]). Asynchronous."""
+    _check_dev(frame_scores, block_idx)
+    if frame_scores.dtype != torch.float32 or frame_scores.dim() != 2 or not frame_scores.is_contiguous():
+        raise ValueError("frame_scores must be a dense 2-d float32 tensor")
+    n_blocks, n_frames = frame_scores.shape
+    if block_idx is not None and (block_idx.dtype != torch.int32 or block_idx.numel() != n_blocks):
+        raise ValueError("block_idx must be int32 [n_blocks]")
+    dec = torch.empty(n_blocks, dtype=torch.int32, device=frame_scores.device)
+    qb = torch.empty(n_blocks, dtype=torch.float32, device=frame_scores.device)
+    st = lib().sdvg_worst_frame_route_batch(_ptr(frame_scores), n_blocks, n_frames, float(tau),
+                                            _ptr(block_idx), int(first_block_idx), _ptr(dec),
+                                            _ptr(qb), _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_worst_frame_route_batch")
+    return dec, qb

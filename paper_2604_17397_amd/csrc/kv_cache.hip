@@ -1,0 +1,180 @@
+// KV-cache commit and rollback: bandwidth-bound copy / zero-fill kernels, one launch for all
+// layers and for both K and V. Paper Sec. 3 "Inference flow": an accepted draft is committed
+// to the target's KV cache; a rejected one must leave no trace before the target regenerates.
+#include "sdvg_common.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // one 16-byte chunk
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;   // 16-byte chunks per thread per loop trip (loads issued together)
+
+struct RowMap {   // maps a (layer, token, head) row of 128 bf16 = 16 chunks into the cache
+  int64_t layer_stride, token_stride, head_stride;  // elements
+  int64_t first_token;                              // first destination token
+  int32_t n_tokens, n_heads;
+};
+
+// Destination element offset of 16-byte chunk g of the dense [L][n_tokens][H][128] index space.
+__device__ __forceinline__ int64_t dst_offset(const RowMap &m, int64_t g) {
+  const int64_t row = g >> 4;
+  const int c = static_cast<int>(g & 15);
+  const int64_t lt = row / m.n_heads;
+  const int h = static_cast<int>(row - lt * m.n_heads);
+  const int64_t l = lt / m.n_tokens;
+  const int64_t t = lt - l * m.n_tokens;
+  return l * m.layer_stride + (m.first_token + t) * m.token_stride + h * m.head_stride + c * 8;
+}
+
+// Contiguous fast path: every layer's destination range is one dense run of chunks_per_layer
+// chunks (token-major cache with head_stride == 128, token_stride == H*128).
+// grid = (blocks_per_layer, n_layers, 2): z selects K or V.
+__global__ __launch_bounds__(kThreads) void kv_commit_dense_kernel(
+    const u32x4 *__restrict__ k_src, const u32x4 *__restrict__ v_src, u32x4 *__restrict__ k_dst,
+    u32x4 *__restrict__ v_dst, int64_t chunks_per_layer, int64_t dst_layer_stride_chunks,
+    int64_t dst_first_chunk) {
+  const u32x4 *src = (blockIdx.z == 0 ? k_src : v_src) + blockIdx.y * chunks_per_layer;
+  u32x4 *dst = (blockIdx.z == 0 ? k_dst : v_dst) + blockIdx.y * dst_layer_stride_chunks +
+               dst_first_chunk;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  for (; i + (kUnroll - 1) * stride < chunks_per_layer; i += kUnroll * stride) {
+    u32x4 r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) r[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) __builtin_nontemporal_store(r[u], dst + i + u * stride);
+  }
+  for (; i < chunks_per_layer; i += stride)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// General strides: one 16-byte chunk per thread per trip, destination computed per chunk.
+__global__ __launch_bounds__(kThreads) void kv_commit_strided_kernel(
+    const u32x4 *__restrict__ k_src, const u32x4 *__restrict__ v_src, uint16_t *__restrict__ k_dst,
+    uint16_t *__restrict__ v_dst, RowMap m, int64_t total_chunks) {
+  const u32x4 *src = blockIdx.y == 0 ? k_src : v_src;
+  uint16_t *dst = blockIdx.y == 0 ? k_dst : v_dst;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; g < total_chunks;
+       g += stride)
+    *reinterpret_cast<u32x4 *>(dst + dst_offset(m, g)) = __builtin_nontemporal_load(src + g);
+}
+
+__global__ __launch_bounds__(kThreads) void kv_zero_dense_kernel(
+    u32x4 *__restrict__ k_dst, u32x4 *__restrict__ v_dst, int64_t chunks_per_layer,
+    int64_t dst_layer_stride_chunks, int64_t dst_first_chunk) {
+  u32x4 *dst = (blockIdx.z == 0 ? k_dst : v_dst) + blockIdx.y * dst_layer_stride_chunks +
+               dst_first_chunk;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < chunks_per_layer;
+       i += stride)
+    __builtin_nontemporal_store(zero, dst + i);
+}
+
+__global__ __launch_bounds__(kThreads) void kv_zero_strided_kernel(uint16_t *__restrict__ k_dst,
+                                                                   uint16_t *__restrict__ v_dst,
+                                                                   RowMap m, int64_t total_chunks) {
+  uint16_t *dst = blockIdx.y == 0 ? k_dst : v_dst;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; g < total_chunks;
+       g += stride)
+    *reinterpret_cast<u32x4 *>(dst + dst_offset(m, g)) = zero;
+}
+
+int validate_cache(const sdvg_kv_cache *c) {
+  if (!c) return SDVG_ERR_NULL;
+  if (!c->k || !c->v) return SDVG_ERR_NULL;
+  if (c->head_dim != 128) return SDVG_ERR_UNSUPPORTED;
+  if (c->n_layers <= 0 || c->n_heads <= 0 || c->block_tokens <= 0 || c->capacity_tokens <= 0)
+    return SDVG_ERR_SHAPE;
+  if (c->cache_len < 0 || c->cache_len > c->capacity_tokens) return SDVG_ERR_RANGE;
+  if (c->head_stride < 128 || c->token_stride < 128 || c->layer_stride < 128) return SDVG_ERR_SHAPE;
+  if ((c->head_stride | c->token_stride | c->layer_stride) & 7) return SDVG_ERR_ALIGN;
+  if (!sdvg::aligned16(c->k) || !sdvg::aligned16(c->v)) return SDVG_ERR_ALIGN;
+  return SDVG_OK;
+}
+
+bool dense_token_major(const sdvg_kv_cache *c) {
+  return c->head_stride == 128 && c->token_stride == static_cast<int64_t>(c->n_heads) * 128;
+}
+
+// Blocks per layer: enough 256-thread blocks to fill the chip several times over, but no more
+// than there are unrolled trips of work.
+int blocks_for(int64_t chunks_per_layer, int n_layers) {
+  const int64_t per_block = static_cast<int64_t>(kThreads) * kUnroll;
+  int64_t want = (chunks_per_layer + per_block - 1) / per_block;
+  int64_t cap = (256 * 16 + 2 * n_layers - 1) / (2 * n_layers);  // ~16 blocks per CU in total
+  if (cap < 1) cap = 1;
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  return static_cast<int>(want);
+}
+
+}  // namespace
+
+extern "C" int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk,
+                              int32_t slot, void *stream) {
+  int st = validate_cache(cache);
+  if (st != SDVG_OK) return st;
+  if (!k_blk || !v_blk) return SDVG_ERR_NULL;
+  if (!sdvg::aligned16(k_blk) || !sdvg::aligned16(v_blk)) return SDVG_ERR_ALIGN;
+  const int64_t T = cache->block_tokens;
+  if (slot < 0 || slot * T != cache->cache_len || (slot + 1) * T > cache->capacity_tokens)
+    return SDVG_ERR_RANGE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t chunks_per_layer = T * cache->n_heads * 16;
+  if (dense_token_major(cache)) {
+    dim3 grid(blocks_for(chunks_per_layer, cache->n_layers), cache->n_layers, 2);
+    hipLaunchKernelGGL(kv_commit_dense_kernel, grid, dim3(kThreads), 0, s,
+                       static_cast<const u32x4 *>(k_blk), static_cast<const u32x4 *>(v_blk),
+                       static_cast<u32x4 *>(cache->k), static_cast<u32x4 *>(cache->v),
+                       chunks_per_layer, cache->layer_stride / 8,
+                       slot * T * cache->token_stride / 8);
+  } else {
+    RowMap m{cache->layer_stride, cache->token_stride, cache->head_stride, slot * T,
+             static_cast<int32_t>(T), cache->n_heads};
+    const int64_t total = chunks_per_layer * cache->n_layers;
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(kv_commit_strided_kernel, dim3(static_cast<unsigned>(blocks), 2),
+                       dim3(kThreads), 0, s, static_cast<const u32x4 *>(k_blk),
+                       static_cast<const u32x4 *>(v_blk), static_cast<uint16_t *>(cache->k),
+                       static_cast<uint16_t *>(cache->v), m, total);
+  }
+  SDVG_HIP_CHECK(hipGetLastError());
+  cache->cache_len = (slot + 1) * T;
+  return SDVG_OK;
+}
+
+extern "C" int sdvg_kv_rollback(sdvg_kv_cache *cache, int64_t new_len, void *stream) {
+  int st = validate_cache(cache);
+  if (st != SDVG_OK) return st;
+  if (new_len < 0 || new_len > cache->cache_len) return SDVG_ERR_RANGE;
+  const int64_t n_tok = cache->cache_len - new_len;
+  if (n_tok == 0) return SDVG_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t chunks_per_layer = n_tok * cache->n_heads * 16;
+  if (dense_token_major(cache)) {
+    dim3 grid(blocks_for(chunks_per_layer, cache->n_layers), cache->n_layers, 2);
+    hipLaunchKernelGGL(kv_zero_dense_kernel, grid, dim3(kThreads), 0, s,
+                       static_cast<u32x4 *>(cache->k), static_cast<u32x4 *>(cache->v),
+                       chunks_per_layer, cache->layer_stride / 8,
+                       new_len * cache->token_stride / 8);
+  } else {
+    RowMap m{cache->layer_stride, cache->token_stride, cache->head_stride, new_len,
+             static_cast<int32_t>(n_tok), cache->n_heads};
+    const int64_t total = chunks_per_layer * cache->n_layers;
+    int64_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(kv_zero_strided_kernel, dim3(static_cast<unsigned>(blocks), 2),
+                       dim3(kThreads), 0, s, static_cast<uint16_t *>(cache->k),
+                       static_cast<uint16_t *>(cache->v), m, total);
+  }
+  SDVG_HIP_CHECK(hipGetLastError());
+  cache->cache_len = new_len;
+  return SDVG_OK;
+}

@@ -1,0 +1,147 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+and rejects bad arguments on the host before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2604_17397_amd as pkg
+    if not os.path.exists(pkg.binding.LIB_PATH):
+        from paper_2604_17397_amd import build
+        build.build()
+    return pkg
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sdvg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sdvg_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_calls():
+    syms = declared_symbols()
+    for name in ("sdvg_block_attn", "sdvg_kv_commit", "sdvg_kv_rollback", "sdvg_worst_frame_route"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol(P):
+    L = ctypes.CDLL(P.binding.LIB_PATH)
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+
+
+def test_status_strings(P):
+    assert P.status_string(0) == "SDVG_OK"
+    for code in range(-6, 0):
+        assert P.status_string(code).startswith("SDVG_ERR_")
+    assert P.lib().sdvg_version() >= 100
+
+
+def make_desc(P, **kw):
+    d = P.binding.sdvg_attn_desc(n_q=8, n_blk=8, n_heads=2, head_dim=128,
+                                 q_token_stride=256, q_head_stride=128,
+                                 o_token_stride=256, o_head_stride=128,
+                                 kv_token_stride=256, kv_head_stride=128,
+                                 blk_token_stride=256, blk_head_stride=128,
+                                 scale=128 ** -0.5, dtype=0)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+FAKE = 0x1000  # a 16-byte aligned non-null address; never dereferenced (validation fails first)
+
+
+@pytest.mark.parametrize("kw,args,expect", [
+    (dict(), dict(q=None), -1),
+    (dict(), dict(out=None), -1),
+    (dict(), dict(k_cache=None, cache_len=8), -1),
+    (dict(head_dim=64), dict(), -5),
+    (dict(dtype=7), dict(), -5),
+    (dict(n_q=0), dict(), -2),
+    (dict(n_blk=0), dict(), -2),
+    (dict(n_heads=0), dict(), -2),
+    (dict(q_token_stride=100), dict(), -2),
+    (dict(q_token_stride=260), dict(), -4),
+    (dict(kv_head_stride=132), dict(cache_len=8), -4),
+    (dict(), dict(q=FAKE + 8), -4),
+    (dict(), dict(cache_len=-1), -3),
+    (dict(scale=0.0), dict(), -3),
+    (dict(scale=float("nan")), dict(), -3),
+])
+def test_block_attn_rejects_bad_arguments(P, kw, args, expect):
+    d = make_desc(P, **kw)
+    a = dict(q=FAKE, k_cache=FAKE, v_cache=FAKE, k_blk=FAKE, v_blk=FAKE, cache_len=0, out=FAKE)
+    a.update(args)
+    st = P.lib().sdvg_block_attn(ctypes.byref(d), a["q"], a["k_cache"], a["v_cache"], a["k_blk"],
+                                 a["v_blk"], a["cache_len"], a["out"], None)
+    assert st == expect, P.status_string(st)
+
+
+def make_cache(P, **kw):
+    c = P.binding.sdvg_kv_cache(k=FAKE, v=FAKE, n_layers=2, n_heads=2, head_dim=128, block_tokens=4,
+                                capacity_tokens=12, cache_len=4, layer_stride=12 * 256,
+                                token_stride=256, head_stride=128)
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+@pytest.mark.parametrize("kw,slot,blk,expect", [
+    (dict(k=None), 1, FAKE, -1),
+    (dict(), 1, None, -1),
+    (dict(head_dim=64), 1, FAKE, -5),
+    (dict(n_layers=0), 1, FAKE, -2),
+    (dict(token_stride=257), 1, FAKE, -4),
+    (dict(), 1, FAKE + 2, -4),
+    (dict(), 0, FAKE, -3),      # slot already filled
+    (dict(), 2, FAKE, -3),      # would leave a hole
+    (dict(), -1, FAKE, -3),
+    (dict(cache_len=12), 3, FAKE, -3),   # full
+    (dict(cache_len=13), 1, FAKE, -3),   # inconsistent descriptor
+])
+def test_kv_commit_rejects_bad_arguments(P, kw, slot, blk, expect):
+    c = make_cache(P, **kw)
+    before = c.cache_len
+    st = P.lib().sdvg_kv_commit(ctypes.byref(c), blk, blk, slot, None)
+    assert st == expect, P.status_string(st)
+    assert c.cache_len == before   # state untouched on error
+
+
+@pytest.mark.parametrize("new_len,expect", [(-1, -3), (5, -3), (4, 0)])
+def test_kv_rollback_argument_checks(P, new_len, expect):
+    c = make_cache(P)
+    st = P.lib().sdvg_kv_rollback(ctypes.byref(c), new_len, None)   # new_len == cache_len: no launch
+    assert st == expect
+    assert c.cache_len == 4
+
+
+@pytest.mark.parametrize("scores,n,tau,blk,expect", [
+    (None, 12, -0.7, 1, -1), (FAKE, 0, -0.7, 1, -2), (FAKE, 12, float("nan"), 1, -3),
+    (FAKE, 12, -0.7, -1, -3), (FAKE + 2, 12, -0.7, 1, -4)])
+def test_route_rejects_bad_arguments(P, scores, n, tau, blk, expect):
+    assert P.lib().sdvg_worst_frame_route(scores, n, tau, blk, None, None) == expect
+
+
+def test_route_batch_rejects_bad_arguments(P):
+    f = P.lib().sdvg_worst_frame_route_batch
+    assert f(None, 4, 12, -0.7, None, 0, FAKE, None, None) == -1
+    assert f(FAKE, 4, 12, -0.7, None, 0, None, None, None) == -1
+    assert f(FAKE, 0, 12, -0.7, None, 0, FAKE, None, None) == -2
+    assert f(FAKE, 4, 0, -0.7, None, 0, FAKE, None, None) == -2
+    assert f(FAKE, 4, 12, float("nan"), None, 0, FAKE, None, None) == -3
+    assert f(FAKE, 4, 12, -0.7, None, -2, FAKE, None, None) == -3
+
+
+def test_missing_library_fails_loudly(P, monkeypatch):
+    import paper_2604_17397_amd.binding as b
+    monkeypatch.setattr(b, "_LIB", None)
+    monkeypatch.setattr(b, "LIB_PATH", "/nonexistent/libsdvg.so")
+    with pytest.raises(RuntimeError):
+        b.lib()
