@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the SDVG hot path on one MI355X.
+
+One step = one video block's worth of the hot path at the 14B target shape (40 layers x 40
+heads x 128, 4680 tokens per block, 6 cached blocks -> 32760 keys):
+    S x L = 4 x 40 block-attention calls (each layer attends over its own slice of a real
+    [40][7*4680][40][128] K/V cache), then the worst-frame router on 12 frame scores, the commit
+    of the block's K/V into slot 6 of all 40 layers, and the rollback that removes it again.
+Inputs are synthetic (seeded torch RNG on the device) and resident in HBM before timing.
+
+Prints ONE JSON line. `value` is whole-step throughput in attention TFLOP/s (algorithmic
+FLOPs 4*n_q*n_k*d*H per call over the full step time, router/commit/rollback included).
+`roofline` is the attention kernel against the bf16 dense MFMA peak, from HIP-event timing of
+the launches inside the timed region; `hbm_kernels` gives commit/rollback GB/s the same way.
+`cpu_baseline` times the fp64 oracle on a bounded row sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="target", choices=["target", "drafter", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--denoise-steps", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by heads with no exchange; "
+              "see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import sdvg_inputs as si
+    import paper_2604_17397_amd as P
+    from paper_2604_17397_amd import build as sdvg_build
+
+    if not os.path.exists(P.binding.LIB_PATH):
+        sdvg_build.build()
+    P.lib()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = si.CONFIGS[args.workload]
+    H, T, L, D = cfg["n_heads"], cfg["block_tokens"], cfg["n_layers"], cfg["head_dim"]
+    nb = cfg["cached_blocks"]
+    S = args.denoise_steps
+    c_len = nb * T
+    n_k = c_len + T
+    cap = (nb + 1) * T
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(si.SEED)
+
+    def randn_bf16(*shape):
+        out = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        flat = out.view(-1)
+        step = 1 << 26
+        for lo in range(0, flat.numel(), step):
+            n = min(step, flat.numel() - lo)
+            flat[lo:lo + n] = torch.randn(n, generator=gen, device=dev, dtype=torch.float32)
+        return out
+
+    k_all = randn_bf16(L, cap, H, D)
+    v_all = randn_bf16(L, cap, H, D)
+    cache = P.KVCache(k_all, v_all, T, cache_len=c_len)
+    k_blk = randn_bf16(L, T, H, D)
+    v_blk = randn_bf16(L, T, H, D)
+    q = randn_bf16(T, H, D)
+    out = torch.empty_like(q)
+    n_rounds = args.steps + args.warmup
+    scores = torch.from_numpy(si.frame_scores_correlated(si.SEED, n_rounds)).to(dev)
+    tau = -0.7
+
+    flops_call = si.attn_flops(T, n_k, H, D)
+    payload = 2.0 * L * T * H * D * 2   # bytes of K+V of one block over all layers
+
+    def step(i, ev=None):
+        if ev:
+            ev[0].record()
+        for _ in range(S):
+            for l in range(L):
+                kc, vc = cache.layer(l)
+                P.block_attn(q, kc, vc, k_blk[l], v_blk[l], c_len, out=out)
+        if ev:
+            ev[1].record()
+        dec, _ = P.worst_frame_route(scores[i], tau, nb)
+        if ev:
+            ev[2].record()
+        P.kv_commit(cache, k_blk, v_blk, nb)
+        if ev:
+            ev[3].record()
+        P.kv_rollback(cache, c_len)
+        if ev:
+            ev[4].record()
+        return dec
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    accepted = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        accepted += step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / (args.steps * S * L)
+    route_us = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps * 1e3
+    commit_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+    rollback_ms = sum(e[3].elapsed_time(e[4]) for e in evs) / args.steps
+
+    value = flops_call * S * L / (ms_step * 1e-3) / 1e12
+    attn_tflops = flops_call / (attn_ms * 1e-3) / 1e12
+    commit_gbps = 2 * payload / (commit_ms * 1e-3) / 1e9
+    rollback_gbps = payload / (rollback_ms * 1e-3) / 1e9
+
+    line = {
+        "metric": "block-attn TFLOP/s & % bf16 MFMA peak at 14B shape; KV-commit GB/s",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s-shape block: %d layers x %d heads x %d, %d query tokens x %d keys "
+                               "(cache %d + block %d), %d denoising steps, then route + commit + rollback"
+                               % (args.workload, L, H, D, T, n_k, c_len, T, S),
+                   "attn_calls_per_step": S * L, "attn_flops_per_call": flops_call,
+                   "commit_payload_bytes": payload, "tau": tau},
+        "roofline": {"kernel": "block_attn_bf16_kernel", "bound": "mfma",
+                     "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(attn_ms, 4)},
+        "hbm_kernels": {
+            "kv_commit": {"bound": "hbm", "achieved": round(commit_gbps, 1), "peak": PEAK_HBM_GBPS,
+                          "unit": "GB/s", "frac": round(commit_gbps / PEAK_HBM_GBPS, 4),
+                          "bytes": 2 * payload, "ms": round(commit_ms, 4)},
+            "kv_rollback": {"bound": "hbm", "achieved": round(rollback_gbps, 1), "peak": PEAK_HBM_GBPS,
+                            "unit": "GB/s", "frac": round(rollback_gbps / PEAK_HBM_GBPS, 4),
+                            "bytes": payload, "ms": round(rollback_ms, 4)},
+            "route_us": round(route_us, 1)},
+        "accepted_blocks": int(accepted),
+    }
+
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(np, torch, si, cache, q, k_blk, v_blk, c_len, out, P)
+    print(json.dumps(line))
+
+
+def cpu_baseline(np, torch, si, cache, q, k_blk, v_blk, c_len, out, P):
+    """Time the fp64 oracle on a bounded row sample of layer 0 and check the GPU rows on it."""
+    import oracle
+    from oracle import build as oracle_build
+    oracle_build.build(force=False)
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    kc, vc = cache.layer(0)
+    P.block_attn(q, kc, vc, k_blk[0], v_blk[0], c_len, out=out)
+    torch.cuda.synchronize()
+    hq, hkc, hvc = bits(q), bits(kc[:max(c_len, 1)]), bits(vc[:max(c_len, 1)])
+    hkb, hvb, hout = bits(k_blk[0]), bits(v_blk[0]), bits(out)
+    n_q, H, D = hq.shape
+    n_k = c_len + hkb.shape[0]
+    threads = oracle.num_threads()
+    # aim at roughly 15 s: calibrate on 2 rows, then size the sample
+    rows_all = si.parity_rows(n_q)
+    t = time.perf_counter()
+    oracle.block_attn(hq, hkc, hvc, hkb, hvb, c_len, rows=rows_all[:2])
+    per_row = max((time.perf_counter() - t) / 2, 1e-6)
+    n_rows = int(max(2, min(len(rows_all), 15.0 / per_row)))
+    rows = rows_all[np.linspace(0, len(rows_all) - 1, n_rows).astype(np.int64)]
+    rows = np.unique(rows)
+    t = time.perf_counter()
+    ref = oracle.block_attn(hq, hkc, hvc, hkb, hvb, c_len, rows=rows)
+    dt = time.perf_counter() - t
+    flops = 4.0 * len(rows) * n_k * D * H
+    g = si.bf16_bits_to_f64(hout[rows])
+    err = g - ref
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "%d of %d query rows x all %d heads of layer 0, all %d keys (fp64, OpenMP)"
+                      % (len(rows), n_q, H, n_k),
+            "gpu_vs_oracle_on_sample": {"max_abs_err": float(np.max(np.abs(err))),
+                                        "rel_rms": float(math.sqrt(np.sum(err * err) / np.sum(ref * ref)))}}
+
+
+if __name__ == "__main__":
+    main()
