@@ -17,6 +17,9 @@
 //   raised (and O, l rescaled) when a tile's maximum exceeds it by more than 2^8, which keeps
 //   exp2 arguments <= 8 and removes the rescale from almost every iteration.
 #include <math.h>
+#include <stdlib.h>
+
+#include <type_traits>
 
 #include "sdvg_common.h"
 
@@ -258,6 +261,828 @@ __global__ __launch_bounds__(NW * 64) void block_attn_bf16_kernel(const AttnPara
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Ping-pong kernel: 8 wavefronts in two groups (waves 0-3 and 4-7, one of each per SIMD) that
+// run half an iteration apart, so that on every SIMD one wave is in its matrix phase
+// (PV of tile t, then QK^T of tile t+1) while the other is in its vector phase (softmax of a
+// tile). Workgroup barriers between the phases keep the two groups in lockstep.
+// K/V tiles go global -> LDS directly (global_load_lds_dwordx4, no register staging) into a
+// ring of kNBuf buffers; bank conflicts are avoided by XOR-swizzling the 16-byte chunk index
+// with the row (applied on the global side of the load, undone on the LDS read side).
+constexpr int kNBuf = 3;
+constexpr int kTileBytes = kBN * 256;  // one 64-key x 128-dim bf16 tile, unpadded
+
+
+__device__ __forceinline__ void wait_vmcnt0() {
+  // s_waitcnt vmcnt(0) only (expcnt = 7, lgkmcnt = 15 left unconstrained)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
+// One wave-level 16-byte-per-lane global -> LDS copy: lane i's 16 bytes land at
+// lds_addr + 16 * i. Written as inline assembly so that the compiler does not serialise
+// successive copies with vmcnt(0) waits; completion is awaited explicitly (wait_vmcnt0)
+// before the workgroup barrier that publishes the tile.
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, off"
+      :
+      : "s"(lds_addr), "v"(gptr)
+      : "memory");
+}
+// Same copy with the 64-token pointer step folded in: the 64-bit add sits between the M0 write
+// and the copy (covering the wait state M0 needs) and the stepped pointer is returned.
+__device__ __forceinline__ const char *dma16_step(const char *gptr, uint64_t step, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %1\n\t"
+      "v_lshl_add_u64 %0, %0, 0, %2\n\t"
+      "global_load_lds_dwordx4 %0, off"
+      : "+v"(gptr)
+      : "s"(lds_addr), "s"(step)
+      : "memory");
+  return gptr;
+}
+
+// Workgroup barrier without the fence of __syncthreads (which would also wait for the
+// prefetches still in flight); the compiler-level memory clobbers keep LDS accesses on
+// their side of it.
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+#ifdef SDVG_ATTN_TIMING
+__device__ unsigned long long g_dbg[2 * 12];
+#define TS(i) do { ts[i] = clock64(); } while (0)
+#else
+#define TS(i) do { } while (0)
+#endif
+
+template <int PRIO>
+__global__ __launch_bounds__(512) void block_attn_bf16_pp_kernel(const AttnParams p) {
+#ifdef SDVG_ATTN_TIMING
+  unsigned long long ts[12] = {0}, acc[12] = {0};
+#endif
+  constexpr int kBM = 256;
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  char *lds_base = reinterpret_cast<char *>(smem);  // K ring at 0, V ring after it
+  constexpr int kVBase = kNBuf * kTileBytes;
+  const uint32_t lds_addr0 =
+      static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds_base));
+
+  const int work = (blockIdx.x % 8) * p.work_per_xcd + blockIdx.x / 8;
+  if (work >= p.total_work) return;
+  const int head = work / p.n_qtiles;
+  const int qt = work - head * p.n_qtiles;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool group_b = wave >= 4;
+  const int r32 = lane & 31;
+  const int hh = lane >> 5;
+
+  const int q_row = qt * kBM + wave * 32 + r32;
+  const int q_row_ld = q_row < p.n_q ? q_row : p.n_q - 1;
+  bf16x8 qf[8];
+  {
+    const uint16_t *qp = p.q + q_row_ld * p.q_ts + head * p.q_hs + 8 * hh;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+  }
+
+  const int n_tiles = (p.n_k + kBN - 1) / kBN;
+
+  // ---- loader: each wave-level load writes 1 KB of LDS = 4 tile rows; lane i lands at
+  // row (i / 16), physical chunk (i % 16) of that block, and fetches the logical chunk that
+  // the swizzle maps there. Every lane keeps the global address of its two rows for the K
+  // stream and for the V stream and advances them by 64 tokens per tile; tiles that contain the
+  // cache/block seam or the end of the keys recompute them (rows past the last key are
+  // clamped onto it and masked in the softmax).
+  const char *kc_base = reinterpret_cast<const char *>(p.k_cache + head * p.kv_hs);
+  const char *vc_base = reinterpret_cast<const char *>(p.v_cache + head * p.kv_hs);
+  const char *kb_base = reinterpret_cast<const char *>(p.k_blk + head * p.blk_hs);
+  const char *vb_base = reinterpret_cast<const char *>(p.v_blk + head * p.blk_hs);
+  const uint32_t kv_tsb = static_cast<uint32_t>(p.kv_ts * 2), blk_tsb = static_cast<uint32_t>(p.blk_ts * 2);
+  const int c_len = static_cast<int>(p.cache_len), n_k = p.n_k;
+  const int ld_row_in_blk = lane >> 4, ld_p = lane & 15;
+  // region of tile t: 0 = wholly inside the cache, 1 = wholly inside the block, 2 = mixed/ragged
+  auto region = [&](int t) {
+    const int lo = t * kBN, hi = lo + kBN - 1;
+    return hi < c_len ? 0 : ((lo >= c_len && hi < n_k) ? 1 : 2);
+  };
+  auto row_ptr = [&](int t, int u, bool is_v) -> const char * {
+    const int row = 4 * (wave + 8 * u) + ld_row_in_blk;
+    int j = t * kBN + row;
+    j = j < n_k ? j : n_k - 1;
+    const bool in_cache = j < c_len;
+    const uint32_t jj = static_cast<uint32_t>(in_cache ? j : j - c_len);
+    const uint64_t row_off = static_cast<uint64_t>(jj) * (in_cache ? kv_tsb : blk_tsb);
+    const int chunk = is_v ? (ld_p ^ (4 * (row & 3))) : (ld_p ^ (row & 15));
+    const char *base = is_v ? (in_cache ? vc_base : vb_base) : (in_cache ? kc_base : kb_base);
+    return base + row_off + chunk * 16;
+  };
+  const char *k_ptr[2], *v_ptr[2];
+  // Moves a stream's row pointers from tile t - 1 to tile t.
+  auto advance = [&](const char *(&ptr)[2], int t, bool is_v) {
+    const int r = region(t);
+    if (t > 0 && r != 2 && r == region(t - 1)) {
+      const uint64_t step = static_cast<uint64_t>(kBN) * (r == 0 ? kv_tsb : blk_tsb);
+      ptr[0] += step;
+      ptr[1] += step;
+    } else {
+      ptr[0] = row_ptr(t, 0, is_v);
+      ptr[1] = row_ptr(t, 1, is_v);
+    }
+  };
+  auto issue_k = [&](int kbuf) {
+    dma16(k_ptr[0], lds_addr0 + kbuf * kTileBytes + wave * 1024);
+    dma16(k_ptr[1], lds_addr0 + kbuf * kTileBytes + (wave + 8) * 1024);
+  };
+  auto issue_v = [&](int vbuf) {
+    dma16(v_ptr[0], lds_addr0 + kVBase + vbuf * kTileBytes + wave * 1024);
+    dma16(v_ptr[1], lds_addr0 + kVBase + vbuf * kTileBytes + (wave + 8) * 1024);
+  };
+
+  // ---- LDS read addresses (bytes)
+  int k_off[8];  // K fragment of step s: row r32 (+32 per half tile), chunk (2s+hh) ^ (r32 & 15)
+#pragma unroll
+  for (int s = 0; s < 8; ++s) k_off[s] = r32 * 256 + (((2 * s + hh) ^ (r32 & 15)) * 16);
+  // V^T fragment through the transposing read: a 16-lane group reads 4 key rows x 16 dims and
+  // each lane receives 4 keys of one dim. The lane addressing row k of the group (k = row & 3)
+  // finds logical 32-dim block db in physical 64-byte slot db ^ k of that row.
+  const int i16 = lane & 15, b16 = (lane >> 4) & 1;
+  int v_off[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+    v_off[db] = kVBase + (4 * hh + (i16 >> 2)) * 256 + ((db ^ (i16 >> 2)) * 64) + 32 * b16 +
+                8 * (i16 & 3);
+
+  f32x16 o_acc[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[u][i] = 0.f;
+  float m_run = -INFINITY;
+  float l_run = 0.f;
+  f32x16 s_acc[2];
+  bf16x8 pf[4];
+  const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+
+  auto qk_tile = [&](int kbuf) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_acc[kb][i] = 0.f;
+    const char *kbase = lds_base + kbuf * kTileBytes;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbase + k_off[s] + kb * 32 * 256);
+        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], s_acc[kb], 0, 0, 0);
+      }
+    }
+  };
+
+  auto softmax_tile = [&](int t) {
+    if (t == n_tiles - 1) {
+      const int key0 = t * kBN + 4 * hh;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (key0 + kb * 32 + 8 * (i >> 2) + (i & 3) >= n_k) s_acc[kb][i] = -INFINITY;
+    }
+    float mt = s_acc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s_acc[kb][i]);
+    mt = lane_max32(mt) * p.scale_log2e;
+    if (__builtin_amdgcn_ballot_w64(mt > m_run + kRescaleSlack) != 0) {
+      const float m_new = fmaxf(m_run, mt);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[u][i] *= alpha;
+      l_run *= alpha;
+      m_run = m_new;
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][i], p.scale_log2e, -m_run));
+        const float p1 =
+            __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][i + 1], p.scale_log2e, -m_run));
+        const f32x2 pp = {p0, p1};
+        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l_run, false);
+        pf[kb * 2 + (i >> 3)][i & 7] = pb[0];
+        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = pb[1];
+      }
+    }
+  };
+
+  auto pv_tile = [&](int vbuf) {
+    const char *vbase = lds_base + vbuf * kTileBytes;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const char *vp = vbase + v_off[u] + j * 16 * 256;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4 *)(vp));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4 *)(vp + 8 * 256));
+        const __attribute__((ext_vector_type(8))) short a16 =
+            __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        bf16x8 a;
+        __builtin_memcpy(&a, &a16, sizeof a);
+        o_acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[j], o_acc[u], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- prologue: K(0..2), V(0..1) into the rings, then S(0)
+#pragma unroll
+  for (int t = 0; t < kNBuf; ++t) {
+    if (t < n_tiles) {
+      advance(k_ptr, t, false);
+      issue_k(t);
+      if (t < kNBuf - 1) {
+        advance(v_ptr, t, true);
+        issue_v(t);
+      }
+    }
+  }
+  wait_vmcnt0();
+  wg_barrier();
+  qk_tile(0);
+  if (group_b) wg_barrier();  // group B runs one phase behind group A
+
+  int kb_cur = 0;   // ring slot of K(t)
+  int vb_cur = 0;   // ring slot of V(t)
+  for (int t = 0; t < n_tiles; ++t) {
+    // ---- vector phase: softmax of tile t
+    TS(0);
+    softmax_tile(t);
+    // keep the whole softmax on this side of the barrier (the compiler would otherwise sink
+    // the exponentials into the matrix phase)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(pf[j]));
+    asm volatile("" : "+v"(l_run));
+    TS(1);
+    wait_vmcnt0();  // this wave's loads issued in the previous matrix phase have landed
+    TS(2);
+    wg_barrier();
+    TS(3);
+
+    // ---- matrix phase: prefetch, O += P(t) V(t), S(t+1) = K(t+1) Q^T
+    if (PRIO) __builtin_amdgcn_s_setprio(PRIO);
+    const int kb_next = kb_cur + 1 == kNBuf ? 0 : kb_cur + 1;
+    const int vb_free = vb_cur == 0 ? kNBuf - 1 : vb_cur - 1;  // held V(t-1), free now
+    // K(t+3) replaces K(t), V(t+2) replaces V(t-1): both buffers were last read one phase ago
+    if (t + kNBuf < n_tiles) {
+      advance(k_ptr, t + kNBuf, false);
+      TS(8);
+      issue_k(kb_cur);
+      TS(9);
+    }
+    if (t + kNBuf - 1 < n_tiles) {
+      advance(v_ptr, t + kNBuf - 1, true);
+      TS(10);
+      issue_v(vb_free);
+    }
+    TS(4);
+    pv_tile(vb_cur);
+    TS(5);
+    if (t + 1 < n_tiles) qk_tile(kb_next);
+    if (PRIO) __builtin_amdgcn_s_setprio(0);
+    kb_cur = kb_next;
+    vb_cur = vb_cur + 1 == kNBuf ? 0 : vb_cur + 1;
+    TS(6);
+    if (!(group_b && t == n_tiles - 1)) wg_barrier();
+    TS(7);
+#ifdef SDVG_ATTN_TIMING
+    if (t >= 100 && t < 164) {
+      for (int i = 0; i < 7; ++i) acc[i] += ts[i + 1] - ts[i];
+      acc[7] += ts[8] - ts[3];   // advance K
+      acc[8] += ts[9] - ts[8];   // issue K
+      acc[9] += ts[10] - ts[9];  // advance V
+      acc[10] += ts[4] - ts[10]; // issue V
+    }
+#endif
+  }
+#ifdef SDVG_ATTN_TIMING
+  if (work == 0 && lane == 0 && (wave == 0 || wave == 4))
+    for (int i = 0; i < 11; ++i) g_dbg[(wave / 4) * 12 + i] = acc[i];
+#endif
+
+  // ---- epilogue
+  const float l_tot = lane_sum32(l_run);
+  const float inv_l = 1.0f / l_tot;
+  if (q_row < p.n_q) {
+    uint16_t *op = p.out + q_row * p.o_ts + head * p.o_hs + 4 * hh;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int db = u;
+        const f32x4 o4 = {o_acc[u][4 * g] * inv_l, o_acc[u][4 * g + 1] * inv_l,
+                          o_acc[u][4 * g + 2] * inv_l, o_acc[u][4 * g + 3] * inv_l};
+        const bf16x4 ob = __builtin_convertvector(o4, bf16x4);
+        *reinterpret_cast<bf16x4 *>(op + 32 * db + 8 * g) = ob;
+      }
+    }
+  }
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Ping-pong kernel, second form: rings of 4 K and 4 V tiles with compile-time slot numbers (the
+// tile loop is unrolled by 4, so every LDS address is a per-lane base register plus an
+// immediate), one tile index for both DMA streams, and an explicitly software-pipelined matrix
+// phase: the LDS reads of the next group of 4 MFMA operands are issued before the current
+// group's 4 MFMAs, and the first group is already fetched at the end of the vector phase.
+constexpr int kRing = 4;
+constexpr float kPSumLimit = 1048576.0f;  // 2^20: a tile whose P sums past this retakes the maximum
+
+template <int PRIO>
+__global__ __launch_bounds__(512) void block_attn_bf16_pp2_kernel(const AttnParams p) {
+#ifdef SDVG_ATTN_TIMING
+  unsigned long long ts[12] = {0}, acc[12] = {0};
+  const unsigned long long k_t0 = clock64(), k_w0 = wall_clock64();
+#endif
+  constexpr int kBM = 256;
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  char *lds_base = reinterpret_cast<char *>(smem);  // K ring at 0, V ring after it
+  constexpr int kVBase = kRing * kTileBytes;
+  const uint32_t lds_addr0 =
+      static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds_base));
+
+  const int work = (blockIdx.x % 8) * p.work_per_xcd + blockIdx.x / 8;
+  if (work >= p.total_work) return;
+  const int head = work / p.n_qtiles;
+  const int qt = work - head * p.n_qtiles;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool group_b = wave >= 4;
+  const int r32 = lane & 31;
+  const int hh = lane >> 5;
+
+  const int q_row = qt * kBM + wave * 32 + r32;
+  const int q_row_ld = q_row < p.n_q ? q_row : p.n_q - 1;
+  bf16x8 qf[8];
+  {
+    const uint16_t *qp = p.q + q_row_ld * p.q_ts + head * p.q_hs + 8 * hh;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
+  }
+
+  const int n_k = p.n_k;
+  const int n_tiles = (n_k + kBN - 1) / kBN;
+
+  // ---- loader (see the first ping-pong kernel): lane i of a wave-level copy lands at row
+  // i / 16, physical chunk i % 16 of a 1 KB block and fetches the chunk the swizzle maps there.
+  const char *kc_base = reinterpret_cast<const char *>(p.k_cache + head * p.kv_hs);
+  const char *vc_base = reinterpret_cast<const char *>(p.v_cache + head * p.kv_hs);
+  const char *kb_base = reinterpret_cast<const char *>(p.k_blk + head * p.blk_hs);
+  const char *vb_base = reinterpret_cast<const char *>(p.v_blk + head * p.blk_hs);
+  const uint32_t kv_tsb = static_cast<uint32_t>(p.kv_ts * 2), blk_tsb = static_cast<uint32_t>(p.blk_ts * 2);
+  const int c_len = static_cast<int>(p.cache_len);
+  const int ld_row_in_blk = lane >> 4, ld_p = lane & 15;
+  const int t_seam_lo = c_len / kBN;              // first tile that holds a block token
+  const int t_seam_hi = (c_len + kBN - 1) / kBN;  // first tile wholly inside the block
+  const uint64_t step_c = static_cast<uint64_t>(kBN) * kv_tsb, step_b = static_cast<uint64_t>(kBN) * blk_tsb;
+  const char *k_ptr[2], *v_ptr[2];
+  auto row_ptrs = [&](int t, int u) __attribute__((always_inline)) {
+    const int row = 4 * (wave + 8 * u) + ld_row_in_blk;
+    int j = t * kBN + row;
+    j = j < n_k ? j : n_k - 1;  // rows past the last key re-read it; masked in the softmax
+    const bool in_cache = j < c_len;
+    const uint32_t jj = static_cast<uint32_t>(in_cache ? j : j - c_len);
+    const uint64_t row_off = static_cast<uint64_t>(jj) * (in_cache ? kv_tsb : blk_tsb);
+    k_ptr[u] = (in_cache ? kc_base : kb_base) + row_off + (ld_p ^ (row & 15)) * 16;
+    v_ptr[u] = (in_cache ? vc_base : vb_base) + row_off + (ld_p ^ (4 * (row & 3))) * 16;
+  };
+  // Moves the row pointers to tile t (called with t = 0, 1, 2, ... in order). Tiles that hold
+  // the cache/block seam, the first tile wholly in the block, and the ragged last tile recompute
+  // the pointers; every other tile is one 64-token step from its predecessor.
+  const int t_ragged = n_k / kBN;  // first tile with a row past the last key (== n_tiles if none)
+  auto advance_ptrs = [&](int t) __attribute__((always_inline)) {
+    const bool special = t == 0 || static_cast<unsigned>(t - t_seam_lo) <= static_cast<unsigned>(t_seam_hi - t_seam_lo) ||
+                         t >= t_ragged;
+    if (__builtin_expect(special, 0)) {
+      asm volatile("" ::: "memory");  // a real branch: keep the address arithmetic off the fast path
+      row_ptrs(t, 0);
+      row_ptrs(t, 1);
+    } else {
+      const uint64_t step = t < t_seam_lo ? step_c : step_b;
+      k_ptr[0] += step;
+      k_ptr[1] += step;
+      v_ptr[0] += step;
+      v_ptr[1] += step;
+    }
+  };
+  // Starts copy number i (K rows 0-31, K rows 32-63, V rows 0-31, V rows 32-63 of this wave's
+  // share) of the tile at the row pointers into ring slot `slot`.
+  auto issue_copy = [&](int slot, int i) __attribute__((always_inline)) {
+    const uint32_t dst = lds_addr0 + slot * kTileBytes + wave * 1024 + (i & 1) * 8 * 1024 +
+                         (i >> 1) * kVBase;
+    dma16(i < 2 ? k_ptr[i] : v_ptr[i - 2], dst);
+  };
+  auto issue_tile = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) issue_copy(slot, i);
+  };
+  // Plain tiles: step the pointer by 64 tokens and start the copy in one go.
+  auto step_copy = [&](int slot, int i, uint64_t step) __attribute__((always_inline)) {
+    const uint32_t dst = lds_addr0 + slot * kTileBytes + wave * 1024 + (i & 1) * 8 * 1024 +
+                         (i >> 1) * kVBase;
+    if (i < 2)
+      k_ptr[i] = dma16_step(k_ptr[i], step, dst);
+    else
+      v_ptr[i - 2] = dma16_step(v_ptr[i - 2], step, dst);
+  };
+
+  // ---- LDS read addresses (bytes)
+  int k_off[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) k_off[s] = r32 * 256 + (((2 * s + hh) ^ (r32 & 15)) * 16);
+  const int i16 = lane & 15, b16 = (lane >> 4) & 1;
+  int v_off[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+    v_off[db] = kVBase + (4 * hh + (i16 >> 2)) * 256 + ((db ^ (i16 >> 2)) * 64) + 32 * b16 +
+                8 * (i16 & 3);
+
+  f32x16 o_acc[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[u][i] = 0.f;
+  float m_run = -INFINITY;
+  float l_run = 0.f;
+  f32x16 s_acc[2];
+  bf16x8 pf[4];
+  bf16x8 fa[4], fb[4];  // two groups of 4 MFMA A-operands: one in use, one being fetched
+  const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // One V^T operand: 16 keys (step j) x dim block u, two transposing reads.
+  auto read_v = [&](bf16x8 &f, int slot, int j, int u) __attribute__((always_inline)) {
+    const char *vp = lds_base + v_off[u] + slot * kTileBytes + j * 16 * 256;
+    const s16x4 lo =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vp));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4 *)(vp + 8 * 256));
+    const __attribute__((ext_vector_type(8))) short a16 =
+        __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    __builtin_memcpy(&f, &a16, sizeof(bf16x8));
+  };
+  auto read_v_group = [&](bf16x8(&f)[4], int slot, int j) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) read_v(f[u], slot, j, u);
+  };
+  // One K operand: dim step s, 32-key half kb.
+  auto read_k = [&](bf16x8 &f, int slot, int s, int kb) __attribute__((always_inline)) {
+    f = *reinterpret_cast<const bf16x8 *>(lds_base + k_off[s] + slot * kTileBytes + kb * 32 * 256);
+  };
+  auto mfma_v = [&](const bf16x8 &f, int j, int u) __attribute__((always_inline)) {
+    o_acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[j], o_acc[u], 0, 0, 0);
+  };
+  auto mfma_k = [&](const bf16x8 &f, int s, int kb) __attribute__((always_inline)) {
+    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[s], s == 0 ? zero16 : s_acc[kb], 0, 0, 0);
+  };
+#define SDVG_SB() __builtin_amdgcn_sched_barrier(0)
+  // s_waitcnt lgkmcnt(0) alone: every LDS read issued so far has returned
+  auto wait_lds0 = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xC07F); };
+  // Matrix-phase building blocks. Operands come in groups of 4 (fa / fb alternate); while a
+  // group's 4 MFMAs run, the next group's LDS reads are issued right after the first two MFMAs
+  // (the wave would otherwise just wait for the matrix pipe), so they have two MFMA times to
+  // land. K group g = dim steps 2g, 2g+1 for both key halves, operand index 2*(s&1) + kb.
+  // PV group j with the V^T operands of step j+1 fetched into `nxt`
+  auto pv_group_fetch_v = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int slot, int j)
+      __attribute__((always_inline)) {
+    SDVG_SB();
+    wait_lds0();  // this group's operands (requested during the previous group) have landed
+    SDVG_SB();
+    mfma_v(cur[0], j, 0);
+    SDVG_SB();
+    read_v(nxt[0], slot, j + 1, 0);
+    read_v(nxt[1], slot, j + 1, 1);
+    SDVG_SB();
+    mfma_v(cur[1], j, 1);
+    SDVG_SB();
+    read_v(nxt[2], slot, j + 1, 2);
+    read_v(nxt[3], slot, j + 1, 3);
+    SDVG_SB();
+    mfma_v(cur[2], j, 2);
+    mfma_v(cur[3], j, 3);
+    SDVG_SB();
+  };
+  // last PV group (j = 3) with the first K group of the next tile fetched into `nxt`
+  auto pv_group_fetch_k = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int kslot, bool fetch)
+      __attribute__((always_inline)) {
+    SDVG_SB();
+    wait_lds0();
+    SDVG_SB();
+    mfma_v(cur[0], 3, 0);
+    SDVG_SB();
+    if (fetch) {
+      read_k(nxt[0], kslot, 0, 0);
+      read_k(nxt[1], kslot, 0, 1);
+    }
+    SDVG_SB();
+    mfma_v(cur[1], 3, 1);
+    SDVG_SB();
+    if (fetch) {
+      read_k(nxt[2], kslot, 1, 0);
+      read_k(nxt[3], kslot, 1, 1);
+    }
+    SDVG_SB();
+    mfma_v(cur[2], 3, 2);
+    mfma_v(cur[3], 3, 3);
+    SDVG_SB();
+  };
+  // QK group g with K group g+1 fetched into `nxt` (no fetch for the last group)
+  auto qk_group = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int kslot, int g)
+      __attribute__((always_inline)) {
+    SDVG_SB();
+    wait_lds0();
+    SDVG_SB();
+    mfma_k(cur[0], 2 * g, 0);
+    SDVG_SB();
+    if (g < 3) {
+      read_k(nxt[0], kslot, 2 * g + 2, 0);
+      read_k(nxt[1], kslot, 2 * g + 2, 1);
+    }
+    SDVG_SB();
+    mfma_k(cur[1], 2 * g, 1);
+    SDVG_SB();
+    if (g < 3) {
+      read_k(nxt[2], kslot, 2 * g + 3, 0);
+      read_k(nxt[3], kslot, 2 * g + 3, 1);
+    }
+    SDVG_SB();
+    mfma_k(cur[2], 2 * g + 1, 0);
+    mfma_k(cur[3], 2 * g + 1, 1);
+    SDVG_SB();
+  };
+  // S(t) = K(t) Q^T with K group 0 already requested into fa
+  auto qk_rest = [&](int slot) __attribute__((always_inline)) {
+    qk_group(fa, fb, slot, 0);
+    qk_group(fb, fa, slot, 1);
+    qk_group(fa, fb, slot, 2);
+    qk_group(fb, fa, slot, 3);
+  };
+
+  // P^T(t) = exp2(S^T(t) * scale*log2e - m) in bf16 (B-operand order) and the row-sum share.
+  // Fast path: no maximum is computed at all. The running maximum m may lag the true one; P is
+  // formed against it, and only if the tile's sum of P comes out huge (a logit more than ~2^15
+  // above m, or m still -inf on the first tile) does the wave take the slow path, which finds
+  // the true maximum, rescales O and l, and forms P again. The result is the same softmax up to
+  // rounding, because numerator and denominator carry the same factor 2^-m.
+  // The three stages (fma, exp2, convert + sum) are kept apart so that dependent instructions
+  // are far from each other in the in-order issue stream.
+  auto form_p = [&]() __attribute__((always_inline)) -> float {
+    const float neg_m = -m_run;
+    float dl[2] = {0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float pexp[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) pexp[i] = __builtin_fmaf(s_acc[kb][i], p.scale_log2e, neg_m);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) pexp[i] = __builtin_amdgcn_exp2f(pexp[i]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const f32x2 pp = {pexp[i], pexp[i + 1]};
+        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+        dl[kb] = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, dl[kb], false);
+        pf[kb * 2 + (i >> 3)][i & 7] = pb[0];
+        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = pb[1];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    return dl[0] + dl[1];
+  };
+  auto softmax_tile = [&](int t, auto plain_c) __attribute__((always_inline)) {
+    if (!decltype(plain_c)::value && t == n_tiles - 1) {
+      const int key0 = t * kBN + 4 * hh;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (key0 + kb * 32 + 8 * (i >> 2) + (i & 3) >= n_k) s_acc[kb][i] = -INFINITY;
+    }
+    float dl = form_p();
+    if (__builtin_amdgcn_ballot_w64(!(dl < kPSumLimit)) != 0) {
+      float m4[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) m4[c] = fmaxf(s_acc[0][c], s_acc[1][c]);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 4; i < 16; ++i) m4[i & 3] = fmaxf(m4[i & 3], s_acc[kb][i]);
+      float mt = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+      mt = lane_max32(mt) * p.scale_log2e;
+      const float m_new = fmaxf(m_run, mt);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // exp2(-inf) = 0 on the first tile
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[u][i] *= alpha;
+      l_run *= alpha;
+      m_run = m_new;
+      dl = form_p();
+    }
+    l_run += dl;
+  };
+
+  // One tile: vector phase (softmax of S(t)), barrier, matrix phase (prefetch of tile t+3,
+  // O += P(t) V(t), S(t+1) = K(t+1) Q^T), barrier. R = t % 4 is the ring slot of tile t.
+  // `plain_c` marks the common case, decided by the caller: tile t+3 exists and is one fixed
+  // 64-token step after tile t+2 (no seam, not ragged), so the body runs without any
+  // conditional; otherwise the general body handles the seam, the tail and the last tiles.
+  uint64_t fast_step = 3 < t_seam_lo ? step_c : step_b;
+  // `slot` is tile t's ring slot, t % 4: a compile-time constant in the unrolled plain loop
+  // (every LDS address is then base register + immediate), a run-time value otherwise.
+  auto tile_body = [&](auto slot, auto plain_c, int t) __attribute__((always_inline)) {
+    const int R = slot;
+    const int Rn = (R + 1) % kRing;
+    constexpr bool kPlain = decltype(plain_c)::value;
+    TS(0);
+    softmax_tile(t, plain_c);
+    read_v_group(fa, R, 0);  // first operands of the matrix phase, fetched ahead of the barrier
+    // keep the whole softmax on this side of the barrier
+#pragma unroll
+    for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(pf[j]));
+    asm volatile("" : "+v"(l_run));
+    TS(1);
+    wait_vmcnt0();  // this wave's copies issued in the previous matrix phase have landed
+    TS(2);
+    wg_barrier();
+    TS(3);
+    if (PRIO == 1) __builtin_amdgcn_s_setprio(1);
+    if (PRIO == 2) __builtin_amdgcn_s_setprio(0);
+    const bool more = kPlain || t + 1 < n_tiles;
+    const bool prefetch = kPlain || t + 3 < n_tiles;
+    const int Rp = (R + 3) % kRing;
+    // After each of the first four MFMA groups one copy of tile t+3 is started: the matrix
+    // pipe is still busy with the group's last MFMA, so these few instructions cost nothing.
+    if (!kPlain && prefetch) advance_ptrs(t + 3);
+    pv_group_fetch_v(fa, fb, R, 0);
+    if (kPlain)
+      step_copy(Rp, 0, fast_step);
+    else if (prefetch)
+      issue_copy(Rp, 0);
+    pv_group_fetch_v(fb, fa, R, 1);
+    if (kPlain)
+      step_copy(Rp, 1, fast_step);
+    else if (prefetch)
+      issue_copy(Rp, 1);
+    TS(4);
+    pv_group_fetch_v(fa, fb, R, 2);
+    if (kPlain)
+      step_copy(Rp, 2, fast_step);
+    else if (prefetch)
+      issue_copy(Rp, 2);
+    pv_group_fetch_k(fb, fa, Rn, more);
+    if (kPlain)
+      step_copy(Rp, 3, fast_step);
+    else if (prefetch)
+      issue_copy(Rp, 3);
+    TS(5);
+    if (more) qk_rest(Rn);
+    if (PRIO == 1) __builtin_amdgcn_s_setprio(0);
+    if (PRIO == 2) __builtin_amdgcn_s_setprio(1);
+    TS(6);
+    if (kPlain || !(group_b && !more)) wg_barrier();
+    TS(7);
+#ifdef SDVG_ATTN_TIMING
+    if (t >= 100 && t < 164) {
+      for (int i = 0; i < 7; ++i) acc[i] += ts[i + 1] - ts[i];
+    }
+#endif
+  };
+  // Tiles that need the general body: those whose prefetch target t+3 touches the seam
+  // [t_seam_lo, t_seam_hi], is ragged, or does not exist.
+  const int g_lo = t_seam_lo - 3, g_hi = t_seam_hi - 3;
+  const int g_end = (t_ragged < n_tiles ? t_ragged : n_tiles) - 3;
+  auto next_general = [&](int x) __attribute__((always_inline)) -> int {
+    if (x >= g_lo && x <= g_hi) return x;
+    const int e = x > g_end ? x : g_end;
+    return (x < g_lo && g_lo < e) ? g_lo : e;
+  };
+  // ---- prologue: tiles 0..2 into the rings, then S(0)
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    if (t < n_tiles) {
+      advance_ptrs(t);
+      issue_tile(t);
+    }
+  }
+  wait_vmcnt0();
+  wg_barrier();
+  read_k(fa[0], 0, 0, 0);
+  read_k(fa[1], 0, 0, 1);
+  read_k(fa[2], 0, 1, 0);
+  read_k(fa[3], 0, 1, 1);
+  qk_rest(0);
+  if (group_b) wg_barrier();  // group B runs one phase behind group A
+
+  for (int t = 0; t < n_tiles;) {
+    const int t_stop = next_general(t);  // tiles [t, t_stop) are plain
+    if ((t & 3) == 0 && t + 4 <= t_stop) {
+      fast_step = t + 3 < t_seam_lo ? step_c : step_b;
+      do {
+        tile_body(std::integral_constant<int, 0>{}, std::true_type{}, t);
+        tile_body(std::integral_constant<int, 1>{}, std::true_type{}, t + 1);
+        tile_body(std::integral_constant<int, 2>{}, std::true_type{}, t + 2);
+        tile_body(std::integral_constant<int, 3>{}, std::true_type{}, t + 3);
+        t += 4;
+      } while (t + 4 <= t_stop);
+    } else {
+      tile_body(t & 3, std::false_type{}, t);
+      ++t;
+    }
+  }
+#ifdef SDVG_ATTN_TIMING
+  if (work == 0 && lane == 0 && (wave == 0 || wave == 4))
+  {
+    acc[7] = clock64() - k_t0;
+    acc[8] = wall_clock64() - k_w0;
+    for (int i = 0; i < 11; ++i) g_dbg[(wave / 4) * 12 + i] = acc[i];
+  }
+#endif
+
+  // ---- epilogue
+  const float l_tot = lane_sum32(l_run);
+  const float inv_l = 1.0f / l_tot;
+  if (q_row < p.n_q) {
+    uint16_t *op = p.out + q_row * p.o_ts + head * p.o_hs + 4 * hh;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 o4 = {o_acc[u][4 * g] * inv_l, o_acc[u][4 * g + 1] * inv_l,
+                          o_acc[u][4 * g + 2] * inv_l, o_acc[u][4 * g + 3] * inv_l};
+        const bf16x4 ob = __builtin_convertvector(o4, bf16x4);
+        *reinterpret_cast<bf16x4 *>(op + 32 * u + 8 * g) = ob;
+      }
+    }
+  }
+}
+
+template <int PRIO>
+int launch_bf16_pp2(const AttnParams &p_in, hipStream_t s) {
+  AttnParams p = p_in;
+  p.n_qtiles = (p.n_q + 255) / 256;
+  p.total_work = p.n_qtiles * p.n_heads;
+  p.work_per_xcd = (p.total_work + 7) / 8;
+  constexpr size_t lds_bytes = 2 * kRing * kTileBytes;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SDVG_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_pp2_kernel<PRIO>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(block_attn_bf16_pp2_kernel<PRIO>, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes,
+                     s, p);
+  SDVG_HIP_CHECK(hipGetLastError());
+  return SDVG_OK;
+}
+
+template <int PRIO>
+int launch_bf16_pp(const AttnParams &p_in, hipStream_t s) {
+  AttnParams p = p_in;
+  p.n_qtiles = (p.n_q + 255) / 256;
+  p.total_work = p.n_qtiles * p.n_heads;
+  p.work_per_xcd = (p.total_work + 7) / 8;
+  constexpr size_t lds_bytes = 2 * kNBuf * kTileBytes;
+  static bool attr_set = false;
+  if (!attr_set) {
+    SDVG_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_pp_kernel<PRIO>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(block_attn_bf16_pp_kernel<PRIO>, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes,
+                     s, p);
+  SDVG_HIP_CHECK(hipGetLastError());
+  return SDVG_OK;
+}
+
 template <int NW>
 int launch_bf16(const AttnParams &p_in, hipStream_t s) {
   AttnParams p = p_in;
@@ -279,6 +1104,12 @@ int launch_bf16(const AttnParams &p_in, hipStream_t s) {
 }
 
 }  // namespace
+
+#ifdef SDVG_ATTN_TIMING
+extern "C" int sdvg_debug_timing(unsigned long long *host16) {
+  return static_cast<int>(hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_dbg), sizeof(g_dbg)));
+}
+#endif
 
 extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cache,
                                const void *v_cache, const void *k_blk, const void *v_blk,
@@ -326,5 +1157,16 @@ extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const 
   p.n_k = static_cast<int32_t>(cache_len + desc->n_blk);
   p.n_heads = desc->n_heads;
   p.scale_log2e = desc->scale * 1.4426950408889634f;
-  return launch_bf16<8>(p, static_cast<hipStream_t>(stream));
+  static const int variant = [] {
+    const char *e = getenv("SDVG_ATTN_VARIANT");
+    return e ? atoi(e) : 0;
+  }();
+  if (variant == 4) return launch_bf16<4>(p, static_cast<hipStream_t>(stream));
+  if (variant == 20) return launch_bf16_pp2<0>(p, static_cast<hipStream_t>(stream));
+  if (variant == 21) return launch_bf16_pp2<1>(p, static_cast<hipStream_t>(stream));
+  if (variant == 22) return launch_bf16_pp2<2>(p, static_cast<hipStream_t>(stream));
+  if (variant == 10) return launch_bf16_pp<0>(p, static_cast<hipStream_t>(stream));
+  if (variant == 11) return launch_bf16_pp<1>(p, static_cast<hipStream_t>(stream));
+  if (variant == 1) return launch_bf16<8>(p, static_cast<hipStream_t>(stream));
+  return launch_bf16_pp2<1>(p, static_cast<hipStream_t>(stream));
 }
