@@ -315,10 +315,26 @@ __device__ __forceinline__ void wg_barrier() {
 }
 
 #ifdef SDVG_ATTN_TIMING
-__device__ unsigned long long g_dbg[2 * 12];
-#define TS(i) do { ts[i] = clock64(); } while (0)
+__device__ unsigned long long g_dbg[2 * 12 + 16];
+__device__ unsigned long long g_dbg2[128];
+#if SDVG_ATTN_TIMING == 3
+#define TS(i) do { } while (0)
+#else
+#define TS(i)                                                                       \
+  do {                                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                              \
+    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(ts[i])::"memory"); \
+    __builtin_amdgcn_sched_barrier(0);                                              \
+  } while (0)
+#endif
+#if SDVG_ATTN_TIMING == 2
+#define TSX(i) TS(i)
+#else
+#define TSX(i) do { } while (0)
+#endif
 #else
 #define TS(i) do { } while (0)
+#define TSX(i) do { } while (0)
 #endif
 
 template <int PRIO>
@@ -739,6 +755,9 @@ __global__ __launch_bounds__(512) void block_attn_bf16_pp2_kernel(const AttnPara
 
   // One V^T operand: 16 keys (step j) x dim block u, two transposing reads.
   auto read_v = [&](bf16x8 &f, int slot, int j, int u) __attribute__((always_inline)) {
+#ifdef SDVG_ABL_NOVREAD
+    if (j > 0) { f = qf[u]; return; }
+#endif
     const char *vp = lds_base + v_off[u] + slot * kTileBytes + j * 16 * 256;
     const s16x4 lo =
         __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vp));
@@ -748,18 +767,23 @@ __global__ __launch_bounds__(512) void block_attn_bf16_pp2_kernel(const AttnPara
         __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     __builtin_memcpy(&f, &a16, sizeof(bf16x8));
   };
-  auto read_v_group = [&](bf16x8(&f)[4], int slot, int j) __attribute__((always_inline)) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) read_v(f[u], slot, j, u);
-  };
   // One K operand: dim step s, 32-key half kb.
   auto read_k = [&](bf16x8 &f, int slot, int s, int kb) __attribute__((always_inline)) {
+#ifdef SDVG_ABL_NOKREAD
+    if (s > 1) { f = qf[s]; return; }
+#endif
     f = *reinterpret_cast<const bf16x8 *>(lds_base + k_off[s] + slot * kTileBytes + kb * 32 * 256);
   };
   auto mfma_v = [&](const bf16x8 &f, int j, int u) __attribute__((always_inline)) {
+#ifdef SDVG_ABL_HALFPV
+    if (u & 1) { asm volatile("" :: "v"(f)); return; }
+#endif
     o_acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[j], o_acc[u], 0, 0, 0);
   };
   auto mfma_k = [&](const bf16x8 &f, int s, int kb) __attribute__((always_inline)) {
+#ifdef SDVG_ABL_HALFQK
+    if (s & 1) { asm volatile("" :: "v"(f)); return; }
+#endif
     s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[s], s == 0 ? zero16 : s_acc[kb], 0, 0, 0);
   };
 #define SDVG_SB() __builtin_amdgcn_sched_barrier(0)
@@ -769,61 +793,20 @@ __global__ __launch_bounds__(512) void block_attn_bf16_pp2_kernel(const AttnPara
   // group's 4 MFMAs run, the next group's LDS reads are issued right after the first two MFMAs
   // (the wave would otherwise just wait for the matrix pipe), so they have two MFMA times to
   // land. K group g = dim steps 2g, 2g+1 for both key halves, operand index 2*(s&1) + kb.
-  // PV group j with the V^T operands of step j+1 fetched into `nxt`
-  auto pv_group_fetch_v = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int slot, int j)
+  // QK group g; K group g+1 (or, after the last group, V group 0 of slot vslot) goes into `nxt`
+  auto qk_group = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int kslot, int g, int vslot)
       __attribute__((always_inline)) {
     SDVG_SB();
     wait_lds0();  // this group's operands (requested during the previous group) have landed
-    SDVG_SB();
-    mfma_v(cur[0], j, 0);
-    SDVG_SB();
-    read_v(nxt[0], slot, j + 1, 0);
-    read_v(nxt[1], slot, j + 1, 1);
-    SDVG_SB();
-    mfma_v(cur[1], j, 1);
-    SDVG_SB();
-    read_v(nxt[2], slot, j + 1, 2);
-    read_v(nxt[3], slot, j + 1, 3);
-    SDVG_SB();
-    mfma_v(cur[2], j, 2);
-    mfma_v(cur[3], j, 3);
-    SDVG_SB();
-  };
-  // last PV group (j = 3) with the first K group of the next tile fetched into `nxt`
-  auto pv_group_fetch_k = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int kslot, bool fetch)
-      __attribute__((always_inline)) {
-    SDVG_SB();
-    wait_lds0();
-    SDVG_SB();
-    mfma_v(cur[0], 3, 0);
-    SDVG_SB();
-    if (fetch) {
-      read_k(nxt[0], kslot, 0, 0);
-      read_k(nxt[1], kslot, 0, 1);
-    }
-    SDVG_SB();
-    mfma_v(cur[1], 3, 1);
-    SDVG_SB();
-    if (fetch) {
-      read_k(nxt[2], kslot, 1, 0);
-      read_k(nxt[3], kslot, 1, 1);
-    }
-    SDVG_SB();
-    mfma_v(cur[2], 3, 2);
-    mfma_v(cur[3], 3, 3);
-    SDVG_SB();
-  };
-  // QK group g with K group g+1 fetched into `nxt` (no fetch for the last group)
-  auto qk_group = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int kslot, int g)
-      __attribute__((always_inline)) {
-    SDVG_SB();
-    wait_lds0();
     SDVG_SB();
     mfma_k(cur[0], 2 * g, 0);
     SDVG_SB();
     if (g < 3) {
       read_k(nxt[0], kslot, 2 * g + 2, 0);
       read_k(nxt[1], kslot, 2 * g + 2, 1);
+    } else {
+      read_v(nxt[0], vslot, 0, 0);
+      read_v(nxt[1], vslot, 0, 1);
     }
     SDVG_SB();
     mfma_k(cur[1], 2 * g, 1);
@@ -831,74 +814,121 @@ __global__ __launch_bounds__(512) void block_attn_bf16_pp2_kernel(const AttnPara
     if (g < 3) {
       read_k(nxt[2], kslot, 2 * g + 3, 0);
       read_k(nxt[3], kslot, 2 * g + 3, 1);
+    } else {
+      read_v(nxt[2], vslot, 0, 2);
+      read_v(nxt[3], vslot, 0, 3);
     }
     SDVG_SB();
     mfma_k(cur[2], 2 * g + 1, 0);
     mfma_k(cur[3], 2 * g + 1, 1);
     SDVG_SB();
   };
-  // S(t) = K(t) Q^T with K group 0 already requested into fa
-  auto qk_rest = [&](int slot) __attribute__((always_inline)) {
-    qk_group(fa, fb, slot, 0);
-    qk_group(fb, fa, slot, 1);
-    qk_group(fa, fb, slot, 2);
-    qk_group(fb, fa, slot, 3);
+  // x = s * scale*log2e - m, in place, for elements 2e and 2e+1 of the 32 scores of this lane
+  auto shift_pair = [&](int e) __attribute__((always_inline)) {
+#ifdef SDVG_ABL_NOSHIFT
+    return;
+#endif
+    const int kb = e >> 3, i = (e & 7) * 2;
+    s_acc[kb][i] = __builtin_fmaf(s_acc[kb][i], p.scale_log2e, -m_run);
+    s_acc[kb][i + 1] = __builtin_fmaf(s_acc[kb][i + 1], p.scale_log2e, -m_run);
+  };
+  // PV group j with the V^T operands of step j+1 fetched into `nxt` (none after j = 3). With
+  // `shift` the fresh scores of the next tile are moved to the log2 domain on the side: two
+  // elements after each MFMA, in issue slots the wave would spend waiting for the matrix pipe.
+  auto pv_group = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int slot, int j, bool shift)
+      __attribute__((always_inline)) {
+    SDVG_SB();
+    wait_lds0();
+    SDVG_SB();
+    mfma_v(cur[0], j, 0);
+    SDVG_SB();
+    if (j < 3) {
+      read_v(nxt[0], slot, j + 1, 0);
+      read_v(nxt[1], slot, j + 1, 1);
+    }
+    if (shift) shift_pair(4 * j);
+    SDVG_SB();
+    mfma_v(cur[1], j, 1);
+    SDVG_SB();
+    if (j < 3) {
+      read_v(nxt[2], slot, j + 1, 2);
+      read_v(nxt[3], slot, j + 1, 3);
+    }
+    if (shift) shift_pair(4 * j + 1);
+    SDVG_SB();
+    mfma_v(cur[2], j, 2);
+    SDVG_SB();
+    if (shift) shift_pair(4 * j + 2);
+    SDVG_SB();
+    mfma_v(cur[3], j, 3);
+    SDVG_SB();
+    if (shift) shift_pair(4 * j + 3);
+    SDVG_SB();
   };
 
-  // P^T(t) = exp2(S^T(t) * scale*log2e - m) in bf16 (B-operand order) and the row-sum share.
-  // Fast path: no maximum is computed at all. The running maximum m may lag the true one; P is
-  // formed against it, and only if the tile's sum of P comes out huge (a logit more than ~2^15
-  // above m, or m still -inf on the first tile) does the wave take the slow path, which finds
-  // the true maximum, rescales O and l, and forms P again. The result is the same softmax up to
-  // rounding, because numerator and denominator carry the same factor 2^-m.
-  // The three stages (fma, exp2, convert + sum) are kept apart so that dependent instructions
-  // are far from each other in the in-order issue stream.
+  // Vector phase: P^T = exp2(S^T * scale*log2e - m) rounded to bf16 in B-operand order, plus
+  // this lane's share of the row sum, taken over the ROUNDED probabilities so that numerator
+  // and denominator of the softmax use the same weights.
+  // No maximum is computed on the fast path: the running maximum m may lag the true one, which
+  // changes nothing (both sides carry the same factor 2^-m) as long as exp2 stays in range.
+  // Only if the tile's sum of P comes out huge (a logit more than ~15 above m in log2 units)
+  // does the wave take the slow path: raise m to the true maximum, rescale O and l, form P again.
+  // The wave issues in order and is alone on the vector ALU during this phase, so the work is
+  // laid out in stages over all 32 scores (shift, exp2, convert, sum with four accumulators):
+  // no instruction depends on one issued just before it.
   auto form_p = [&]() __attribute__((always_inline)) -> float {
+    float pexp[2][16];
     const float neg_m = -m_run;
-    float dl[2] = {0.f, 0.f};
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float pexp[16];
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) pexp[i] = __builtin_fmaf(s_acc[kb][i], p.scale_log2e, neg_m);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < 16; ++i) pexp[kb][i] = __builtin_fmaf(s_acc[kb][i], p.scale_log2e, neg_m);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) pexp[i] = __builtin_amdgcn_exp2f(pexp[i]);
-      __builtin_amdgcn_sched_barrier(0);
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        const f32x2 pp = {pexp[i], pexp[i + 1]};
-        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-        dl[kb] = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, dl[kb], false);
-        pf[kb * 2 + (i >> 3)][i & 7] = pb[0];
-        pf[kb * 2 + (i >> 3)][(i & 7) + 1] = pb[1];
+      for (int i = 0; i < 16; ++i) pexp[kb][i] = __builtin_amdgcn_exp2f(pexp[kb][i]);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x2 pb[2][8];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const f32x2 pp = {pexp[kb][2 * i], pexp[kb][2 * i + 1]};
+        pb[kb][i] = __builtin_convertvector(pp, bf16x2);
       }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    return dl[0] + dl[1];
+    __builtin_amdgcn_sched_barrier(0);
+    float dl[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        dl[i & 3] = __builtin_amdgcn_fdot2_f32_bf16(pb[kb][i], ones, dl[i & 3], false);
+        pf[kb * 2 + (i >> 2)][(i & 3) * 2] = pb[kb][i][0];
+        pf[kb * 2 + (i >> 2)][(i & 3) * 2 + 1] = pb[kb][i][1];
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    return (dl[0] + dl[1]) + (dl[2] + dl[3]);
   };
-  auto softmax_tile = [&](int t, auto plain_c) __attribute__((always_inline)) {
-    if (!decltype(plain_c)::value && t == n_tiles - 1) {
-      const int key0 = t * kBN + 4 * hh;
+  auto tile_max = [&]() __attribute__((always_inline)) -> float {
+    float m4[4];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+    for (int c = 0; c < 4; ++c) m4[c] = fmaxf(s_acc[0][c], s_acc[1][c]);
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (key0 + kb * 32 + 8 * (i >> 2) + (i & 3) >= n_k) s_acc[kb][i] = -INFINITY;
-    }
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 4; i < 16; ++i) m4[i & 3] = fmaxf(m4[i & 3], s_acc[kb][i]);
+    return lane_max32(fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3])));
+  };
+  auto softmax_tile = [&]() __attribute__((always_inline)) {
+#ifdef SDVG_ABL_NOSOFTMAX
+    l_run += s_acc[0][0];
+    return;
+#endif
     float dl = form_p();
     if (__builtin_amdgcn_ballot_w64(!(dl < kPSumLimit)) != 0) {
-      float m4[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) m4[c] = fmaxf(s_acc[0][c], s_acc[1][c]);
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 4; i < 16; ++i) m4[i & 3] = fmaxf(m4[i & 3], s_acc[kb][i]);
-      float mt = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
-      mt = lane_max32(mt) * p.scale_log2e;
-      const float m_new = fmaxf(m_run, mt);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // exp2(-inf) = 0 on the first tile
+      const float m_new = fmaxf(m_run, tile_max() * p.scale_log2e);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -909,81 +939,144 @@ __global__ __launch_bounds__(512) void block_attn_bf16_pp2_kernel(const AttnPara
     }
     l_run += dl;
   };
+  // Keys past n_k (last tile only) get -inf before the scores are shifted.
+  auto mask_tail = [&](int t) __attribute__((always_inline)) {
+    const int key0 = t * kBN + 4 * hh;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (key0 + kb * 32 + 8 * (i >> 2) + (i & 3) >= n_k) s_acc[kb][i] = -INFINITY;
+  };
 
-  // One tile: vector phase (softmax of S(t)), barrier, matrix phase (prefetch of tile t+3,
-  // O += P(t) V(t), S(t+1) = K(t+1) Q^T), barrier. R = t % 4 is the ring slot of tile t.
-  // `plain_c` marks the common case, decided by the caller: tile t+3 exists and is one fixed
-  // 64-token step after tile t+2 (no seam, not ragged), so the body runs without any
-  // conditional; otherwise the general body handles the seam, the tail and the last tiles.
+  // ---- rare events of the tile loop. Tile t starts the copies of tile t+3 by stepping the row
+  // pointers 64 tokens on. That is wrong when tile t+3 holds the cache/block seam, is the
+  // first tile wholly inside the block, is the ragged last tile, or does not exist; for those
+  // t (t == t_evt) the pointers are set beforehand so that the step lands on the right rows
+  // (past the end: on the last tile again, a harmless redundant copy).
   uint64_t fast_step = 3 < t_seam_lo ? step_c : step_b;
-  // `slot` is tile t's ring slot, t % 4: a compile-time constant in the unrolled plain loop
-  // (every LDS address is then base register + immediate), a run-time value otherwise.
-  auto tile_body = [&](auto slot, auto plain_c, int t) __attribute__((always_inline)) {
-    const int R = slot;
-    const int Rn = (R + 1) % kRing;
-    constexpr bool kPlain = decltype(plain_c)::value;
+  const int g_lo = t_seam_lo - 3, g_hi = t_seam_hi - 3;
+  const int g_end = (t_ragged < n_tiles ? t_ragged : n_tiles) - 3;
+  auto next_event = [&](int x) __attribute__((always_inline)) -> int {
+    if (x >= g_lo && x <= g_hi) return x;
+    const int e = x > g_end ? x : g_end;
+    return (x < g_lo && g_lo < e) ? g_lo : e;
+  };
+  int t_evt = next_event(0);
+  bool mask_next = false;  // the scores produced by this tile's matrix phase need the tail mask
+  auto on_event = [&](int t) __attribute__((always_inline)) {
+    asm volatile("" ::: "memory");  // a real branch: keep this arithmetic off the fast path
+    const int tau = t + 3 < n_tiles ? t + 3 : n_tiles - 1;
+    fast_step = t + 3 >= n_tiles ? 0 : (tau + 1 < t_seam_lo ? step_c : step_b);
+    row_ptrs(tau, 0);
+    row_ptrs(tau, 1);
+    k_ptr[0] -= fast_step;
+    k_ptr[1] -= fast_step;
+    v_ptr[0] -= fast_step;
+    v_ptr[1] -= fast_step;
+    mask_next = t + 1 == n_tiles - 1 && t_ragged < n_tiles;
+    t_evt = next_event(t + 1);
+  };
+
+  // One tile: vector phase (softmax of the shifted S(t)), barrier, matrix phase (copies of tile
+  // t+3 started, S(t+1) = K(t+1) Q^T, then O += P(t) V(t) with S(t+1) shifted on the side),
+  // barrier. R = t % 4, the ring slot of tile t, is a compile-time constant: the loop is
+  // unrolled by 4 and every LDS address is a base register plus an immediate.
+  // The last tile computes a meaningless S(t+1) from a stale slot; nothing reads it.
+#if defined(SDVG_ATTN_TIMING) && SDVG_ATTN_TIMING == 4
+#define TSL(k)                                                                                   \
+  do {                                                                                           \
+    if (t >= 200 && t < 208) {                                                                   \
+      unsigned long long now_;                                                                   \
+      asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(now_)::"memory");               \
+      if (lane == 0)                                                                             \
+        *reinterpret_cast<unsigned long long *>(lds_base + 2 * kRing * kTileBytes + wave * 1024 + \
+                                                ((t - 200) * 8 + (k)) * 8) = now_;               \
+    }                                                                                            \
+  } while (0)
+#else
+#define TSL(k) do { } while (0)
+#endif
+  auto tile_body = [&](auto slot, int t) __attribute__((always_inline)) {
+    constexpr int R = decltype(slot)::value;
+    constexpr int Rn = (R + 1) % kRing;
+    constexpr int Rp = (R + 3) % kRing;
     TS(0);
-    softmax_tile(t, plain_c);
-    read_v_group(fa, R, 0);  // first operands of the matrix phase, fetched ahead of the barrier
+    TSL(0);
+    softmax_tile();
+    TSL(1);
+    // first operands of the matrix phase, fetched ahead of the barrier
+    read_k(fa[0], Rn, 0, 0);
+    read_k(fa[1], Rn, 0, 1);
+    read_k(fa[2], Rn, 1, 0);
+    read_k(fa[3], Rn, 1, 1);
     // keep the whole softmax on this side of the barrier
 #pragma unroll
     for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(pf[j]));
     asm volatile("" : "+v"(l_run));
-    TS(1);
+    TSX(1);
+    TSL(2);
+#ifndef SDVG_ABL_NOVMWAIT
     wait_vmcnt0();  // this wave's copies issued in the previous matrix phase have landed
+#endif
     TS(2);
+    TSL(3);
     wg_barrier();
+    TSL(4);
     TS(3);
     if (PRIO == 1) __builtin_amdgcn_s_setprio(1);
     if (PRIO == 2) __builtin_amdgcn_s_setprio(0);
-    const bool more = kPlain || t + 1 < n_tiles;
-    const bool prefetch = kPlain || t + 3 < n_tiles;
-    const int Rp = (R + 3) % kRing;
+    if (__builtin_expect(t == t_evt, 0)) on_event(t);
     // After each of the first four MFMA groups one copy of tile t+3 is started: the matrix
     // pipe is still busy with the group's last MFMA, so these few instructions cost nothing.
-    if (!kPlain && prefetch) advance_ptrs(t + 3);
-    pv_group_fetch_v(fa, fb, R, 0);
-    if (kPlain)
-      step_copy(Rp, 0, fast_step);
-    else if (prefetch)
-      issue_copy(Rp, 0);
-    pv_group_fetch_v(fb, fa, R, 1);
-    if (kPlain)
-      step_copy(Rp, 1, fast_step);
-    else if (prefetch)
-      issue_copy(Rp, 1);
-    TS(4);
-    pv_group_fetch_v(fa, fb, R, 2);
-    if (kPlain)
-      step_copy(Rp, 2, fast_step);
-    else if (prefetch)
-      issue_copy(Rp, 2);
-    pv_group_fetch_k(fb, fa, Rn, more);
-    if (kPlain)
-      step_copy(Rp, 3, fast_step);
-    else if (prefetch)
-      issue_copy(Rp, 3);
-    TS(5);
-    if (more) qk_rest(Rn);
+    qk_group(fa, fb, Rn, 0, R);
+#ifndef SDVG_ABL_NODMA
+    step_copy(Rp, 0, fast_step);
+#endif
+    qk_group(fb, fa, Rn, 1, R);
+#ifndef SDVG_ABL_NODMA
+    step_copy(Rp, 1, fast_step);
+#endif
+    TSX(4);
+    qk_group(fa, fb, Rn, 2, R);
+#ifndef SDVG_ABL_NODMA
+    step_copy(Rp, 2, fast_step);
+#endif
+    qk_group(fb, fa, Rn, 3, R);  // leaves V group 0 in fa
+#ifndef SDVG_ABL_NODMA
+    step_copy(Rp, 3, fast_step);
+#endif
+    if (__builtin_expect(mask_next, 0)) mask_tail(t + 1);
+    TSX(5);
+    TSL(5);
+    pv_group(fa, fb, R, 0, false);
+    pv_group(fb, fa, R, 1, false);
+    pv_group(fa, fb, R, 2, false);
+    pv_group(fb, fa, R, 3, false);
     if (PRIO == 1) __builtin_amdgcn_s_setprio(0);
     if (PRIO == 2) __builtin_amdgcn_s_setprio(1);
     TS(6);
-    if (kPlain || !(group_b && !more)) wg_barrier();
-    TS(7);
-#ifdef SDVG_ATTN_TIMING
-    if (t >= 100 && t < 164) {
-      for (int i = 0; i < 7; ++i) acc[i] += ts[i + 1] - ts[i];
-    }
+    TSL(6);
+#ifndef SDVG_ABL_NOBAR2
+    wg_barrier();
 #endif
-  };
-  // Tiles that need the general body: those whose prefetch target t+3 touches the seam
-  // [t_seam_lo, t_seam_hi], is ragged, or does not exist.
-  const int g_lo = t_seam_lo - 3, g_hi = t_seam_hi - 3;
-  const int g_end = (t_ragged < n_tiles ? t_ragged : n_tiles) - 3;
-  auto next_general = [&](int x) __attribute__((always_inline)) -> int {
-    if (x >= g_lo && x <= g_hi) return x;
-    const int e = x > g_end ? x : g_end;
-    return (x < g_lo && g_lo < e) ? g_lo : e;
+    TSL(7);
+    TS(7);
+#if defined(SDVG_ATTN_TIMING) && SDVG_ATTN_TIMING != 3
+    if (t >= 100 && t < 164) {
+#if SDVG_ATTN_TIMING == 2
+      for (int i = 0; i < 7; ++i) acc[i] += ts[i + 1] - ts[i];
+#else
+      acc[0] += ts[2] - ts[0];
+      acc[1] += ts[3] - ts[2];
+      acc[2] += ts[6] - ts[3];
+      acc[3] += ts[7] - ts[6];
+#endif
+      acc[9] += ts[0] - ts[11];
+    }
+    ts[11] = ts[7];
+    if ((t & 63) == 0 && work == 0 && lane == 0 && wave == 0) g_dbg[24 + (t >> 6)] = ts[0] - k_t0;
+#endif
   };
   // ---- prologue: tiles 0..2 into the rings, then S(0)
 #pragma unroll
@@ -999,25 +1092,38 @@ __global__ __launch_bounds__(512) void block_attn_bf16_pp2_kernel(const AttnPara
   read_k(fa[1], 0, 0, 1);
   read_k(fa[2], 0, 1, 0);
   read_k(fa[3], 0, 1, 1);
-  qk_rest(0);
+  qk_group(fa, fb, 0, 0, 0);
+  qk_group(fb, fa, 0, 1, 0);
+  qk_group(fa, fb, 0, 2, 0);
+  qk_group(fb, fa, 0, 3, 0);  // (its V read is harmless: slot 0 holds V(0))
+  wait_lds0();
+  if (n_tiles == 1) mask_tail(0);
+  m_run = tile_max() * p.scale_log2e;  // the running maximum starts at tile 0's true maximum
+#ifndef SDVG_ABL_NOBAR2
   if (group_b) wg_barrier();  // group B runs one phase behind group A
+#endif
 
-  for (int t = 0; t < n_tiles;) {
-    const int t_stop = next_general(t);  // tiles [t, t_stop) are plain
-    if ((t & 3) == 0 && t + 4 <= t_stop) {
-      fast_step = t + 3 < t_seam_lo ? step_c : step_b;
-      do {
-        tile_body(std::integral_constant<int, 0>{}, std::true_type{}, t);
-        tile_body(std::integral_constant<int, 1>{}, std::true_type{}, t + 1);
-        tile_body(std::integral_constant<int, 2>{}, std::true_type{}, t + 2);
-        tile_body(std::integral_constant<int, 3>{}, std::true_type{}, t + 3);
-        t += 4;
-      } while (t + 4 <= t_stop);
-    } else {
-      tile_body(t & 3, std::false_type{}, t);
-      ++t;
-    }
+  for (int t = 0;;) {
+    tile_body(std::integral_constant<int, 0>{}, t);
+    if (++t == n_tiles) break;
+    tile_body(std::integral_constant<int, 1>{}, t);
+    if (++t == n_tiles) break;
+    tile_body(std::integral_constant<int, 2>{}, t);
+    if (++t == n_tiles) break;
+    tile_body(std::integral_constant<int, 3>{}, t);
+    if (++t == n_tiles) break;
   }
+  wait_vmcnt0();               // the redundant copies of the last tiles must not outlive the wave
+#ifndef SDVG_ABL_NOBAR2
+  if (!group_b) wg_barrier();  // pairs with group B's extra barrier at the start
+#endif
+#if defined(SDVG_ATTN_TIMING) && SDVG_ATTN_TIMING == 4
+  __syncthreads();
+  if (work == 0 && lane == 0 && (wave == 0 || wave == 4))
+    for (int i = 0; i < 64; ++i)
+      g_dbg2[(wave / 4) * 64 + i] = *reinterpret_cast<unsigned long long *>(
+          lds_base + 2 * kRing * kTileBytes + wave * 1024 + i * 8);
+#endif
 #ifdef SDVG_ATTN_TIMING
   if (work == 0 && lane == 0 && (wave == 0 || wave == 4))
   {
@@ -1051,7 +1157,11 @@ int launch_bf16_pp2(const AttnParams &p_in, hipStream_t s) {
   p.n_qtiles = (p.n_q + 255) / 256;
   p.total_work = p.n_qtiles * p.n_heads;
   p.work_per_xcd = (p.total_work + 7) / 8;
+#if defined(SDVG_ATTN_TIMING) && SDVG_ATTN_TIMING == 4
+  constexpr size_t lds_bytes = 2 * kRing * kTileBytes + 8192;
+#else
   constexpr size_t lds_bytes = 2 * kRing * kTileBytes;
+#endif
   static bool attr_set = false;
   if (!attr_set) {
     SDVG_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_pp2_kernel<PRIO>),
@@ -1106,6 +1216,9 @@ int launch_bf16(const AttnParams &p_in, hipStream_t s) {
 }  // namespace
 
 #ifdef SDVG_ATTN_TIMING
+extern "C" int sdvg_debug_timing2(unsigned long long *host128) {
+  return static_cast<int>(hipMemcpyFromSymbol(host128, HIP_SYMBOL(g_dbg2), sizeof(g_dbg2)));
+}
 extern "C" int sdvg_debug_timing(unsigned long long *host16) {
   return static_cast<int>(hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_dbg), sizeof(g_dbg)));
 }
