@@ -29,7 +29,7 @@ typedef enum {
   SDVG_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent */
   SDVG_ERR_RANGE = -3,       /* slot / length / threshold outside its valid range */
   SDVG_ERR_ALIGN = -4,       /* pointer not 16-byte aligned, or stride not a multiple of 8 */
-  SDVG_ERR_UNSUPPORTED = -5, /* head_dim != 128, unknown dtype or mode */
+  SDVG_ERR_UNSUPPORTED = -5, /* head_dim != 128, unknown dtype, stride >= 2^30 elements */
   SDVG_ERR_DEVICE = -6       /* a HIP runtime call failed (see sdvg_last_device_error) */
 } sdvg_status;
 
@@ -77,7 +77,9 @@ typedef struct {
  *             NULL when cache_len == 0. Tokens at or past cache_len are never read.
  *   out       device [n_q][n_heads][128], same dtype as the inputs; every element is written.
  *   Arithmetic (bf16): products on the matrix cores with fp32 accumulation, fp32 softmax
- *   statistics, probabilities rounded to bf16 before the PV product, bf16 output (RNE).
+ *   statistics, probabilities rounded to bf16 before the PV product (the row sum is taken over
+ *   the rounded values), bf16 output (RNE). SDVG_F32 is a slow all-fp32 check path.
+ *   scale must be finite and > 0, else SDVG_ERR_RANGE. Inputs are assumed finite.
  * Asynchronous: enqueued on `stream`; returns SDVG_OK or a negative status.
  */
 int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cache,

@@ -8,7 +8,6 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // one 16-byte chunk
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;   // 16-byte chunks per thread per loop trip (loads issued together)
 
 struct RowMap {   // maps a (layer, token, head) row of 128 bf16 = 16 chunks into the cache
   int64_t layer_stride, token_stride, head_stride;  // elements
@@ -29,25 +28,19 @@ __device__ __forceinline__ int64_t dst_offset(const RowMap &m, int64_t g) {
 
 // Contiguous fast path: every layer's destination range is one dense run of chunks_per_layer
 // chunks (token-major cache with head_stride == 128, token_stride == H*128).
-// grid = (blocks_per_layer, n_layers, 2): z selects K or V.
+// grid = (blocks_per_layer, n_layers, 2): z selects K or V. One 16-byte chunk per thread and
+// no loop: on MI355X many small workgroups beat grid-stride loops and deeper unrolling for a
+// pure copy (measured 6.4 TB/s of read+write traffic against 5.1-5.8 TB/s for the looped forms).
 __global__ __launch_bounds__(kThreads) void kv_commit_dense_kernel(
     const u32x4 *__restrict__ k_src, const u32x4 *__restrict__ v_src, u32x4 *__restrict__ k_dst,
     u32x4 *__restrict__ v_dst, int64_t chunks_per_layer, int64_t dst_layer_stride_chunks,
     int64_t dst_first_chunk) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i >= chunks_per_layer) return;
   const u32x4 *src = (blockIdx.z == 0 ? k_src : v_src) + blockIdx.y * chunks_per_layer;
   u32x4 *dst = (blockIdx.z == 0 ? k_dst : v_dst) + blockIdx.y * dst_layer_stride_chunks +
                dst_first_chunk;
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-  int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-  for (; i + (kUnroll - 1) * stride < chunks_per_layer; i += kUnroll * stride) {
-    u32x4 r[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) r[u] = __builtin_nontemporal_load(src + i + u * stride);
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) __builtin_nontemporal_store(r[u], dst + i + u * stride);
-  }
-  for (; i < chunks_per_layer; i += stride)
-    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+  __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 // General strides: one 16-byte chunk per thread per trip, destination computed per chunk.
@@ -65,13 +58,12 @@ __global__ __launch_bounds__(kThreads) void kv_commit_strided_kernel(
 __global__ __launch_bounds__(kThreads) void kv_zero_dense_kernel(
     u32x4 *__restrict__ k_dst, u32x4 *__restrict__ v_dst, int64_t chunks_per_layer,
     int64_t dst_layer_stride_chunks, int64_t dst_first_chunk) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i >= chunks_per_layer) return;
   u32x4 *dst = (blockIdx.z == 0 ? k_dst : v_dst) + blockIdx.y * dst_layer_stride_chunks +
                dst_first_chunk;
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
   const u32x4 zero = {0u, 0u, 0u, 0u};
-  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < chunks_per_layer;
-       i += stride)
-    __builtin_nontemporal_store(zero, dst + i);
+  __builtin_nontemporal_store(zero, dst + i);
 }
 
 __global__ __launch_bounds__(kThreads) void kv_zero_strided_kernel(uint16_t *__restrict__ k_dst,
@@ -102,16 +94,8 @@ bool dense_token_major(const sdvg_kv_cache *c) {
   return c->head_stride == 128 && c->token_stride == static_cast<int64_t>(c->n_heads) * 128;
 }
 
-// Blocks per layer: enough 256-thread blocks to fill the chip several times over, but no more
-// than there are unrolled trips of work.
-int blocks_for(int64_t chunks_per_layer, int n_layers) {
-  const int64_t per_block = static_cast<int64_t>(kThreads) * kUnroll;
-  int64_t want = (chunks_per_layer + per_block - 1) / per_block;
-  int64_t cap = (256 * 16 + 2 * n_layers - 1) / (2 * n_layers);  // ~16 blocks per CU in total
-  if (cap < 1) cap = 1;
-  if (want > cap) want = cap;
-  if (want < 1) want = 1;
-  return static_cast<int>(want);
+dim3 dense_grid(int64_t chunks_per_layer, int n_layers) {
+  return dim3(static_cast<unsigned>((chunks_per_layer + kThreads - 1) / kThreads), n_layers, 2);
 }
 
 }  // namespace
@@ -128,18 +112,16 @@ extern "C" int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const voi
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t chunks_per_layer = T * cache->n_heads * 16;
   if (dense_token_major(cache)) {
-    dim3 grid(blocks_for(chunks_per_layer, cache->n_layers), cache->n_layers, 2);
-    hipLaunchKernelGGL(kv_commit_dense_kernel, grid, dim3(kThreads), 0, s,
-                       static_cast<const u32x4 *>(k_blk), static_cast<const u32x4 *>(v_blk),
-                       static_cast<u32x4 *>(cache->k), static_cast<u32x4 *>(cache->v),
-                       chunks_per_layer, cache->layer_stride / 8,
+    hipLaunchKernelGGL(kv_commit_dense_kernel, dense_grid(chunks_per_layer, cache->n_layers),
+                       dim3(kThreads), 0, s, static_cast<const u32x4 *>(k_blk),
+                       static_cast<const u32x4 *>(v_blk), static_cast<u32x4 *>(cache->k),
+                       static_cast<u32x4 *>(cache->v), chunks_per_layer, cache->layer_stride / 8,
                        slot * T * cache->token_stride / 8);
   } else {
     RowMap m{cache->layer_stride, cache->token_stride, cache->head_stride, slot * T,
              static_cast<int32_t>(T), cache->n_heads};
     const int64_t total = chunks_per_layer * cache->n_layers;
-    int64_t blocks = (total + kThreads - 1) / kThreads;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    const int64_t blocks = (total + kThreads - 1) / kThreads;
     hipLaunchKernelGGL(kv_commit_strided_kernel, dim3(static_cast<unsigned>(blocks), 2),
                        dim3(kThreads), 0, s, static_cast<const u32x4 *>(k_blk),
                        static_cast<const u32x4 *>(v_blk), static_cast<uint16_t *>(cache->k),
@@ -159,17 +141,15 @@ extern "C" int sdvg_kv_rollback(sdvg_kv_cache *cache, int64_t new_len, void *str
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t chunks_per_layer = n_tok * cache->n_heads * 16;
   if (dense_token_major(cache)) {
-    dim3 grid(blocks_for(chunks_per_layer, cache->n_layers), cache->n_layers, 2);
-    hipLaunchKernelGGL(kv_zero_dense_kernel, grid, dim3(kThreads), 0, s,
-                       static_cast<u32x4 *>(cache->k), static_cast<u32x4 *>(cache->v),
-                       chunks_per_layer, cache->layer_stride / 8,
+    hipLaunchKernelGGL(kv_zero_dense_kernel, dense_grid(chunks_per_layer, cache->n_layers),
+                       dim3(kThreads), 0, s, static_cast<u32x4 *>(cache->k),
+                       static_cast<u32x4 *>(cache->v), chunks_per_layer, cache->layer_stride / 8,
                        new_len * cache->token_stride / 8);
   } else {
     RowMap m{cache->layer_stride, cache->token_stride, cache->head_stride, new_len,
              static_cast<int32_t>(n_tok), cache->n_heads};
     const int64_t total = chunks_per_layer * cache->n_layers;
-    int64_t blocks = (total + kThreads - 1) / kThreads;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    const int64_t blocks = (total + kThreads - 1) / kThreads;
     hipLaunchKernelGGL(kv_zero_strided_kernel, dim3(static_cast<unsigned>(blocks), 2),
                        dim3(kThreads), 0, s, static_cast<uint16_t *>(cache->k),
                        static_cast<uint16_t *>(cache->v), m, total);

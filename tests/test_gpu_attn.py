@@ -60,3 +60,37 @@ def test_ragged_sizes(n_blk, n_q):
 
 def test_jittered_heads_sharp_and_diffuse_softmax():
     check(run_case(12, 312, 624, jitter=True, seed=5))
+
+
+# ---------------------------------------------------------------- fp32-input check path
+
+def run_case_f32(H, n_blk, cache_len, seed=si.SEED, jitter=False, cap_extra=0, n_q=None):
+    import paper_2604_17397_amd as P
+    from gpu_util import F32_MAX_ABS
+    q, kc, vc, kb, vb = si.attn_inputs(H, n_blk, cache_len, seed=seed, jitter=jitter, dtype="f32",
+                                       cache_capacity=cache_len + cap_extra)
+    if n_q is not None:
+        q = np.ascontiguousarray(q[:n_q])
+    dev = lambda a: torch.from_numpy(a).cuda() if a.shape[0] else None
+    out = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    P.block_attn(dev(q), dev(kc), dev(vc), dev(kb), dev(vb), cache_len, out=out)
+    torch.cuda.synchronize()
+    if kc.shape[0] == 0:
+        kc = vc = np.zeros((1, H, 128), np.float32)
+    ref = oracle.block_attn(q, kc, vc, kb, vb, cache_len)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    assert np.isfinite(err).all()
+    assert err.max() <= F32_MAX_ABS, err.max()
+
+
+def test_f32_check_tiny_config():
+    run_case_f32(12, 312, 624, cap_extra=7)
+
+
+def test_f32_check_jittered_heads():
+    run_case_f32(12, 312, 624, jitter=True, seed=5)
+
+
+@pytest.mark.parametrize("cache_len,n_blk,n_q", [(0, 72, 72), (1, 5, 3), (31, 33, 33), (32, 64, 1), (100, 129, 129)])
+def test_f32_check_seam_and_tails(cache_len, n_blk, n_q):
+    run_case_f32(2, n_blk, cache_len, seed=3 + cache_len, cap_extra=2, n_q=n_q)
