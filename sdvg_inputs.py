@@ -160,3 +160,36 @@ def parity_rows(n_q, head=64, tail=136, every=37):
 def attn_flops(n_q, n_k, n_heads, head_dim=128):
     """Algorithmic FLOPs of one attention call: QK^T and PV, 2 per multiply-add."""
     return 4.0 * n_q * n_k * head_dim * n_heads
+
+
+# ---------------------------------------------------------------- device-side generation
+# The numpy generator above is too slow for the full-size shapes (10^8..10^9 elements); the
+# full-size GPU tests and the benchmark draw N(0,1) with torch's seeded generator on the device
+# and copy the bits back for the oracle, so both sides still see identical inputs.
+
+def device_normal_bf16(shape, seed, tensor_id, device="cuda", head_scale=None, chunk=1 << 26):
+    """N(0,1) bfloat16 tensor of `shape` on `device`; optional per-head fp32 multiplier
+    (shape[-2] must be the head axis). Filled in chunks to bound the fp32 temporary."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed) * 1000003 + int(tensor_id))
+    out = torch.empty(shape, dtype=torch.bfloat16, device=device)
+    flat = out.view(-1)
+    scale = None
+    if head_scale is not None:
+        scale = torch.as_tensor(np.asarray(head_scale, np.float32), device=device)
+    inner = shape[-1] * shape[-2] if len(shape) >= 2 else 1
+    step = max(inner, (chunk // inner) * inner)
+    for lo in range(0, flat.numel(), step):
+        n = min(step, flat.numel() - lo)
+        x = torch.randn(n, generator=gen, device=device, dtype=torch.float32)
+        if scale is not None:
+            x = (x.view(-1, shape[-2], shape[-1]) * scale.view(1, -1, 1)).reshape(-1)
+        flat[lo:lo + n] = x
+    return out
+
+
+def bits_from_device(t):
+    """bfloat16 torch tensor -> uint16 numpy bit patterns (host)."""
+    import torch
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

@@ -1,0 +1,148 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot run the whole problem (3.1 TFLOP-equivalent per call in fp64), so attention is
+checked on sampled query rows -- rows are independent, so the sampled rows are checked exactly
+as in the small tests: all heads, all keys. Inputs are drawn on the device with a seeded
+generator and the same bits are handed to the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import sdvg_inputs as si
+from gpu_util import BF16_MAX_ABS, BF16_REL_RMS, attn_errors
+
+pytestmark = pytest.mark.gpu
+
+T = 4680  # 3 latent frames x 30 x 52 tokens
+
+
+def attn_case(H, cache_len, seed, jitter=False, heads=None, rows=None):
+    import paper_2604_17397_amd as P
+    hs = [si.head_scales(seed, H, w) for w in range(3)] if jitter else [None] * 3
+    q = si.device_normal_bf16((T, H, 128), seed, si.TID_Q, head_scale=hs[0])
+    kb = si.device_normal_bf16((T, H, 128), seed, si.TID_K_BLK, head_scale=hs[1])
+    vb = si.device_normal_bf16((T, H, 128), seed, si.TID_V_BLK, head_scale=hs[2])
+    cap = cache_len + 17   # a few poisoned tokens past cache_len
+    kc = si.device_normal_bf16((cap, H, 128), seed, si.TID_K_CACHE, head_scale=hs[1])
+    vc = si.device_normal_bf16((cap, H, 128), seed, si.TID_V_CACHE, head_scale=hs[2])
+    kc[cache_len:].view(torch.int16).fill_(0x7FC1)
+    vc[cache_len:].view(torch.int16).fill_(0x7FC1)
+    out = torch.full((T, H, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.block_attn(q, kc, vc, kb, vb, cache_len, out=out)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out.float()).any()          # every element written, no poison read
+    rows = si.parity_rows(T) if rows is None else rows
+    hsel = slice(None) if heads is None else heads
+    f = si.bits_from_device
+    ref = oracle.block_attn(f(q[:, hsel]), f(kc[:max(cache_len, 1), hsel]), f(vc[:max(cache_len, 1), hsel]),
+                            f(kb[:, hsel]), f(vb[:, hsel]), cache_len, rows=rows)
+    got = f(out[:, hsel])[rows]
+    max_abs, rel = attn_errors(got, ref)
+    assert max_abs <= BF16_MAX_ABS and rel <= BF16_REL_RMS, (max_abs, rel)
+    return max_abs, rel
+
+
+def test_drafter_shape_all_heads_jittered():
+    # 1.3B drafter layer: 12 heads, 4680 queries x (9360 cached + 4680) keys, per-head jitter
+    attn_case(12, 2 * T, seed=101, jitter=True)
+
+
+@pytest.mark.parametrize("k", [0, 1, 6])
+def test_target_shape_all_heads(k):
+    # 14B target layer: 40 heads, cache of k blocks; k = 6 is the headline 4680 x 32760 shape
+    attn_case(40, k * T, seed=200 + k)
+
+
+@pytest.mark.parametrize("k", [2, 3, 4, 5])
+def test_target_shape_cache_sweep_four_heads(k):
+    attn_case(40, k * T, seed=200 + k, heads=[0, 13, 26, 39], rows=si.parity_rows(T)[::3])
+
+
+def test_speculative_round_at_target_shape():
+    """40 layers x 40 heads, 5 cached blocks, draft staged in slot 5, routed, kept or rolled back.
+    Three layers are compared in full against the oracle mirror; every layer is compared on
+    sampled tokens, on the untouched neighbours of the slot and on checksums of the prefix."""
+    import paper_2604_17397_amd as P
+    L, H, nb, cap_blocks = 40, 40, 5, 7
+    cap = cap_blocks * T
+    k = torch.empty((L, cap, H, 128), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    for l in range(L):   # seeded content for the 5 cached blocks, canary words past them
+        k[l, :nb * T] = si.device_normal_bf16((nb * T, H, 128), 300, 1000 + l)
+        v[l, :nb * T] = si.device_normal_bf16((nb * T, H, 128), 300, 2000 + l)
+    k[:, nb * T:].view(torch.int16).fill_(0x7FC1)
+    v[:, nb * T:].view(torch.int16).fill_(0x7FC1)
+    kb = si.device_normal_bf16((L, T, H, 128), 301, si.TID_K_BLK)
+    vb = si.device_normal_bf16((L, T, H, 128), 301, si.TID_V_BLK)
+    cache = P.KVCache(k, v, T, cache_len=nb * T)
+    f = si.bits_from_device
+    full_layers = [0, 17, 39]
+    mirrors = {}
+    for l in full_layers:
+        m = oracle.KVMirror(1, cap, H, 128, T)
+        m.k[0], m.v[0] = f(k[l]), f(v[l])
+        m.cache_len = nb * T
+        mirrors[l] = m
+    prefix_sum = [k[:, :nb * T].view(torch.int16).sum(dtype=torch.int64).item(),
+                  v[:, :nb * T].view(torch.int16).sum(dtype=torch.int64).item()]
+    tok = np.array([0, 1, 63, 64, 2339, T - 2, T - 1])
+
+    def check(after_commit):
+        torch.cuda.synchronize()
+        for l in full_layers:
+            assert np.array_equal(f(k[l]), mirrors[l].k[0]) and np.array_equal(f(v[l]), mirrors[l].v[0])
+        assert cache.cache_len == mirrors[0].cache_len
+        # every layer: prefix untouched, canary after the slot untouched
+        assert k[:, :nb * T].view(torch.int16).sum(dtype=torch.int64).item() == prefix_sum[0]
+        assert v[:, :nb * T].view(torch.int16).sum(dtype=torch.int64).item() == prefix_sum[1]
+        assert (k[:, (nb + 1) * T:].view(torch.int16) == 0x7FC1).all()
+        assert (v[:, (nb + 1) * T:].view(torch.int16) == 0x7FC1).all()
+        # every layer, sampled tokens of the slot against a one-token-at-a-time oracle
+        for l in range(0, L, 3):
+            for t in tok:
+                m1 = oracle.KVMirror(1, 1, H, 128, 1)
+                if after_commit:
+                    assert oracle.kv_commit(m1, f(kb[l, t])[None, None], f(vb[l, t])[None, None], 0) == 0
+                assert np.array_equal(f(k[l, nb * T + t]), m1.k[0, 0])
+                assert np.array_equal(f(v[l, nb * T + t]), m1.v[0, 0])
+
+    # optimistic mode: stage the draft, route, roll back on reject
+    scores = si.frame_scores_correlated(302, 6)
+    for rnd, tau in enumerate((-1.0, -0.7, -0.4)):
+        P.kv_commit(cache, kb, vb, nb)
+        for l in full_layers:
+            assert oracle.kv_commit(mirrors[l], f(kb[l])[None], f(vb[l])[None], nb) == 0
+        check(after_commit=True)
+        dec, qb = P.worst_frame_route(torch.from_numpy(scores[rnd]).cuda(), tau, nb)
+        want = oracle.route(scores[rnd], tau, nb)
+        assert dec == want[0] and qb.view(np.uint32) == want[1].view(np.uint32)
+        # both branches end with the block gone here so that the next round can stage again
+        P.kv_rollback(cache, nb * T)
+        for l in full_layers:
+            assert oracle.kv_rollback(mirrors[l], nb * T) == 0
+        torch.cuda.synchronize()
+        for l in full_layers:
+            assert np.array_equal(f(k[l]), mirrors[l].k[0]) and np.array_equal(f(v[l]), mirrors[l].v[0])
+        assert not k[:, nb * T:(nb + 1) * T].view(torch.int16).any()   # scrubbed in every layer
+        assert not v[:, nb * T:(nb + 1) * T].view(torch.int16).any()
+        # the canary of the rolled-back slot is now zero in the mirrors as well
+        k[:, nb * T:(nb + 1) * T].view(torch.int16).fill_(0x7FC1)
+        v[:, nb * T:(nb + 1) * T].view(torch.int16).fill_(0x7FC1)
+        for l in full_layers:
+            mirrors[l].k[0, nb * T:(nb + 1) * T] = 0x7FC1
+            mirrors[l].v[0, nb * T:(nb + 1) * T] = 0x7FC1
+    assert dec in (0, 1)
+
+
+def test_routing_many_rounds_both_generators():
+    import paper_2604_17397_amd as P
+    for gen in (si.frame_scores_iid, si.frame_scores_correlated):
+        scores = gen(303, 64)
+        for tau in (-1.0, -0.7, -0.4):
+            for b in (0, 5):
+                for r in range(64):
+                    got = P.worst_frame_route(torch.from_numpy(scores[r]).cuda(), tau, b)
+                    want = oracle.route(scores[r], tau, b)
+                    assert got[0] == want[0] and got[1].view(np.uint32) == want[1].view(np.uint32)
