@@ -26,6 +26,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload and
+# scaled by what the same counters read for the commit kernel, a plain copy of known size
+# (profiles/bench_target_pmc.txt). Only valid for the target workload.
+TRAFFIC_TARGET = {"block_attn": 0.9875e9 + 0.0479e9, "kv_commit": 2 * 3.834e9, "kv_rollback": 3.835e9}
 
 
 def main():
@@ -66,24 +70,12 @@ def main():
     n_k = c_len + T
     cap = (nb + 1) * T
 
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(si.SEED)
-
-    def randn_bf16(*shape):
-        out = torch.empty(shape, dtype=torch.bfloat16, device=dev)
-        flat = out.view(-1)
-        step = 1 << 26
-        for lo in range(0, flat.numel(), step):
-            n = min(step, flat.numel() - lo)
-            flat[lo:lo + n] = torch.randn(n, generator=gen, device=dev, dtype=torch.float32)
-        return out
-
-    k_all = randn_bf16(L, cap, H, D)
-    v_all = randn_bf16(L, cap, H, D)
+    k_all = si.device_normal_bf16((L, cap, H, D), si.SEED, si.TID_K_CACHE, device=dev)
+    v_all = si.device_normal_bf16((L, cap, H, D), si.SEED, si.TID_V_CACHE, device=dev)
     cache = P.KVCache(k_all, v_all, T, cache_len=c_len)
-    k_blk = randn_bf16(L, T, H, D)
-    v_blk = randn_bf16(L, T, H, D)
-    q = randn_bf16(T, H, D)
+    k_blk = si.device_normal_bf16((L, T, H, D), si.SEED, si.TID_K_BLK, device=dev)
+    v_blk = si.device_normal_bf16((L, T, H, D), si.SEED, si.TID_V_BLK, device=dev)
+    q = si.device_normal_bf16((T, H, D), si.SEED, si.TID_Q, device=dev)
     out = torch.empty_like(q)
     n_rounds = args.steps + args.warmup
     scores = torch.from_numpy(si.frame_scores_correlated(si.SEED, n_rounds)).to(dev)
@@ -147,15 +139,18 @@ def main():
                    "commit_payload_bytes": payload, "tau": tau},
         "roofline": {"kernel": "block_attn_bf16_kernel", "bound": "mfma",
                      "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": TRAFFIC_TARGET["block_attn"] if args.workload == "target" else None,
                      "avg_launch_ms": round(attn_ms, 4)},
         "hbm_kernels": {
             "kv_commit": {"bound": "hbm", "achieved": round(commit_gbps, 1), "peak": PEAK_HBM_GBPS,
                           "unit": "GB/s", "frac": round(commit_gbps / PEAK_HBM_GBPS, 4),
-                          "bytes": 2 * payload, "ms": round(commit_ms, 4)},
+                          "bytes": 2 * payload, "ms": round(commit_ms, 4),
+                          "traffic": TRAFFIC_TARGET["kv_commit"] if args.workload == "target" else None},
             "kv_rollback": {"bound": "hbm", "achieved": round(rollback_gbps, 1), "peak": PEAK_HBM_GBPS,
                             "unit": "GB/s", "frac": round(rollback_gbps / PEAK_HBM_GBPS, 4),
-                            "bytes": payload, "ms": round(rollback_ms, 4)},
+                            "bytes": payload, "ms": round(rollback_ms, 4),
+                            "traffic": TRAFFIC_TARGET["kv_rollback"] if args.workload == "target" else None},
             "route_us": round(route_us, 1)},
         "accepted_blocks": int(accepted),
     }
