@@ -456,6 +456,8 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     pv_group(fb, fa, R, 1);
     pv_group(fa, fb, R, 2);
     pv_group(fb, fa, R, 3);
+    // let this wave's last MFMAs retire before the partner wave takes over the matrix pipe
+    asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
     __builtin_amdgcn_s_setprio(0);
     wg_barrier();
   };
@@ -469,6 +471,26 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   }
   wait_vmcnt0();
   wg_barrier();
+
+  // A wave whose 32 query rows all lie past n_q (last q-tile of a head) computes nothing: it
+  // only keeps its share of the tile copies going and takes part in the barriers, so that its
+  // SIMD is left to the partner wave.
+  if (qt * kBM + wave * 32 >= p.n_q) {
+    if (group_b) wg_barrier();
+    for (int t = 0; t < n_tiles; ++t) {
+      wait_vmcnt0();
+      wg_barrier();
+      if (t == t_evt) on_event(t);
+      const int rp = (t + 3) & (kRing - 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) step_copy(rp, i, fast_step);
+      wg_barrier();
+    }
+    wait_vmcnt0();
+    if (!group_b) wg_barrier();
+    return;
+  }
+
   read_k(fa[0], 0, 0, 0);
   read_k(fa[1], 0, 0, 1);
   read_k(fa[2], 0, 1, 0);
