@@ -117,7 +117,12 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   const int r32 = lane & 31;
   const int hh = lane >> 5;
 
-  const int q_row = qt * kBM + wave * 32 + r32;
+  // The head's 32-row wave tiles are dealt out evenly over its workgroups, so that when they do
+  // not fill the last workgroup the idle waves are spread one per workgroup: every workgroup of
+  // a head then streams K/V at the same pace and the re-reads stay in the XCD's L2.
+  const int wt_count = p.wt_base + (qt < p.wt_rem ? 1 : 0);
+  const int wt_first = qt * p.wt_base + (qt < p.wt_rem ? qt : p.wt_rem);
+  const int q_row = (wt_first + wave) * 32 + r32;
   const int q_row_ld = q_row < p.n_q ? q_row : p.n_q - 1;
   bf16x8 qf[8];
   {
@@ -472,10 +477,9 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   wait_vmcnt0();
   wg_barrier();
 
-  // A wave whose 32 query rows all lie past n_q (last q-tile of a head) computes nothing: it
-  // only keeps its share of the tile copies going and takes part in the barriers, so that its
-  // SIMD is left to the partner wave.
-  if (qt * kBM + wave * 32 >= p.n_q) {
+  // A wave without a wave tile computes nothing: it only keeps its share of the tile copies
+  // going and takes part in the barriers, so that its SIMD is left to the partner wave.
+  if (wave >= wt_count) {
     if (group_b) wg_barrier();
     for (int t = 0; t < n_tiles; ++t) {
       wait_vmcnt0();
@@ -538,6 +542,9 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
 int launch_bf16(const AttnParams &p_in, hipStream_t s) {
   AttnParams p = p_in;
   p.n_qtiles = (p.n_q + kBM - 1) / kBM;
+  const int n_wt = (p.n_q + 31) / 32;
+  p.wt_base = n_wt / p.n_qtiles;
+  p.wt_rem = n_wt % p.n_qtiles;
   p.total_work = p.n_qtiles * p.n_heads;
   p.work_per_xcd = (p.total_work + 7) / 8;
   constexpr size_t lds_bytes = 2 * kRing * kTileBytes;

@@ -11,6 +11,7 @@ struct AttnParams {
   int64_t q_ts, q_hs, o_ts, o_hs, kv_ts, kv_hs, blk_ts, blk_hs;  // strides in elements
   int64_t cache_len;
   int32_t n_q, n_k, n_heads, n_qtiles, total_work, work_per_xcd;
+  int32_t wt_base, wt_rem;  // 32-row wave tiles per workgroup: wt_base, plus one for the first wt_rem
   float scale_log2e;  // scale * log2(e)
 };
 
