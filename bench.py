@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload and
 # scaled by what the same counters read for the commit kernel, a plain copy of known size
-# (profiles/bench_target_pmc.txt). Only valid for the target workload.
+# (FETCH_SIZE reads half the known bytes, WRITE_SIZE all of them). Only valid for the target workload.
 TRAFFIC_TARGET = {"block_attn": 0.9875e9 + 0.0479e9, "kv_commit": 2 * 3.834e9, "kv_rollback": 3.835e9}
 
 
@@ -42,8 +42,8 @@ def main():
     ap.add_argument("--denoise-steps", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by heads with no exchange; "
-              "see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path shards by heads with no exchange "
+              "inside it); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
