@@ -155,6 +155,20 @@ def main():
         "accepted_blocks": int(accepted),
     }
 
+    # what the matrix cores of this chip deliver with nothing else going on, and at what clock
+    P.probe_mfma(4000)
+    torch.cuda.synchronize()
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pe[0].record()
+    probe_flops, probe_cycles = P.probe_mfma(40000)
+    pe[1].record()
+    torch.cuda.synchronize()
+    probe_ms = pe[0].elapsed_time(pe[1])
+    line["roofline"]["mfma_only_probe"] = {
+        "tflops": round(probe_flops / (probe_ms * 1e-3) / 1e12, 1),
+        "clock_ghz": round(int(probe_cycles.item()) / (probe_ms * 1e-3) / 1e9, 3),
+        "note": "register-only bf16 MFMA loop on the same chip; the 2500 peak assumes 2.4 GHz"}
+
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(np, torch, si, cache, q, k_blk, v_blk, c_len, out, P)
     print(json.dumps(line))

@@ -135,6 +135,20 @@ int sdvg_worst_frame_route_batch(const float *frame_scores, int32_t n_blocks, in
                                  float tau, const int32_t *block_idx, int32_t first_block_idx,
                                  int32_t *decisions_out, float *q_b_out, void *stream);
 
+/*
+ * Measurement aid (no passage of the paper: it exists so that a benchmark can report what the
+ * matrix cores of the chip it runs on deliver, next to the attention kernel's rate). Launches
+ * 256 workgroups of 4 waves (one wave per SIMD of the chip); every wave issues iters x 16 v_mfma_f32_32x32x16_bf16 from
+ * registers and nothing else. Asynchronous on `stream`; the caller times it.
+ *   out        device, at least 65536 floats (n_out = its length): checksums, never read back.
+ *   cycles     device, one uint64: shader clocks wave 0 took (clock = cycles / measured time).
+ *   iters      1 .. 2^24.
+ *   flops_out  host, nullable: the FLOPs the launch performs (256 x 4 x iters x 16 x 32768).
+ * Returns SDVG_OK or a negative status.
+ */
+int sdvg_probe_mfma(float *out, int64_t n_out, uint64_t *cycles, int32_t iters, double *flops_out,
+                    void *stream);
+
 /* Human-readable name of a status code (static storage; never NULL). */
 const char *sdvg_status_string(int status);
 

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     kv_rollback,
     worst_frame_route,
     worst_frame_route_batch,
+    probe_mfma,
     lib,
     status_string,
     SDVG_BF16,

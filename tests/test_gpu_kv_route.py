@@ -166,3 +166,14 @@ def test_route_batch_matches_oracle_for_both_score_generators():
             assert dec[idx == 0].sum() == 0
         dec2, _ = P.worst_frame_route_batch(torch.from_numpy(scores).cuda(), -0.7, first_block_idx=0)
         assert dec2[0].item() == 0
+
+
+def test_mfma_probe_runs():
+    """The MFMA-only measurement kernel: runs, reports its FLOP count and a clock reading."""
+    import paper_2604_17397_amd as P
+    flops, cycles = P.probe_mfma(500)
+    torch.cuda.synchronize()
+    assert flops == 256 * 4 * 500 * 16 * 32768.0
+    assert int(cycles.item()) > 500 * 16 * 8   # at least a quarter of the MFMA-bound cycle count
+    with pytest.raises(P.SdvgError):
+        P.probe_mfma(0)
