@@ -136,6 +136,21 @@ int sdvg_worst_frame_route_batch(const float *frame_scores, int32_t n_blocks, in
                                  int32_t *decisions_out, float *q_b_out, void *stream);
 
 /*
+ * Average-frame routing, the variant the paper's ablation compares with (Sec. 4.3 "Min-frame
+ * vs. average-frame scoring", Table 2): q_b = mean of the block's F per-frame rewards instead
+ * of their minimum; everything else (accept iff q_b >= tau, block 0 always rejected, NaN ->
+ * reject with q_b = quiet NaN, arguments, return values, synchronisation) as in
+ * sdvg_worst_frame_route / _batch. The mean is the fp64 sum of the rewards taken in frame order,
+ * divided by F in fp64 and rounded once to fp32, so it is bit-exact against a sequential loop;
+ * a mean that comes out NaN (+inf and -inf among the rewards) is reported as the same quiet NaN.
+ */
+int sdvg_avg_frame_route(const float *frame_scores, int32_t n_frames, float tau, int32_t block_idx,
+                         float *q_b_out, void *stream);
+int sdvg_avg_frame_route_batch(const float *frame_scores, int32_t n_blocks, int32_t n_frames,
+                               float tau, const int32_t *block_idx, int32_t first_block_idx,
+                               int32_t *decisions_out, float *q_b_out, void *stream);
+
+/*
  * Measurement aid (no passage of the paper: it exists so that a benchmark can report what the
  * matrix cores of the chip it runs on deliver, next to the attention kernel's rate). Launches
  * 256 workgroups of 4 waves (one wave per SIMD of the chip); every wave issues iters x 16 v_mfma_f32_32x32x16_bf16 from

@@ -187,6 +187,12 @@ int sdvg_oracle_route(const float *scores, int64_t n_frames, float tau, int64_t 
     double acc = 0.0;
     for (int64_t i = 0; i < n_frames; ++i) acc += (double)scores[i];
     qb = (float)(acc / (double)n_frames);
+    if (isnan(qb)) { /* +inf and -inf among the scores: same canonical NaN as a NaN score */
+      const uint32_t qnan = 0x7FC00000u;
+      memcpy(&qb, &qnan, sizeof qb);
+      if (q_b_out) *q_b_out = qb;
+      return 0;
+    }
   } else {
     qb = scores[0];
     for (int64_t i = 1; i < n_frames; ++i) {

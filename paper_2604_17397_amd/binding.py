@@ -63,6 +63,10 @@ def lib():
         L.sdvg_worst_frame_route.argtypes = [vp, i32, f32, i32, ctypes.POINTER(f32), vp]
         L.sdvg_worst_frame_route_batch.restype = ctypes.c_int
         L.sdvg_worst_frame_route_batch.argtypes = [vp, i32, i32, f32, vp, i32, vp, vp, vp]
+        L.sdvg_avg_frame_route.restype = ctypes.c_int
+        L.sdvg_avg_frame_route.argtypes = [vp, i32, f32, i32, ctypes.POINTER(f32), vp]
+        L.sdvg_avg_frame_route_batch.restype = ctypes.c_int
+        L.sdvg_avg_frame_route_batch.argtypes = [vp, i32, i32, f32, vp, i32, vp, vp, vp]
         L.sdvg_probe_mfma.restype = ctypes.c_int
         L.sdvg_probe_mfma.argtypes = [vp, i64, vp, i32, ctypes.POINTER(ctypes.c_double), vp]
         L.sdvg_status_string.restype = ctypes.c_char_p
@@ -166,25 +170,27 @@ def kv_rollback(cache, new_len, stream=None):
         raise SdvgError(st, "sdvg_kv_rollback")
 
 
-def worst_frame_route(frame_scores, tau, block_idx, stream=None):
-    """sdvg_worst_frame_route: returns (decision, q_b) with q_b a numpy float32 scalar."""
+def worst_frame_route(frame_scores, tau, block_idx, stream=None, mode="min"):
+    """sdvg_worst_frame_route (mode "min") or sdvg_avg_frame_route (mode "mean"): returns
+    (decision, q_b) with q_b a numpy float32 scalar."""
     import numpy as np
+    fn = {"min": lib().sdvg_worst_frame_route, "mean": lib().sdvg_avg_frame_route}[mode]
     _check_dev(frame_scores)
     if frame_scores.dtype != torch.float32 or frame_scores.dim() != 1 or not frame_scores.is_contiguous():
         raise ValueError("frame_scores must be a dense 1-d float32 tensor")
     qb = np.zeros(1, dtype=np.float32)
-    st = lib().sdvg_worst_frame_route(_ptr(frame_scores), frame_scores.numel(), float(tau),
-                                      int(block_idx),
-                                      qb.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
-                                      _stream_ptr(stream))
+    st = fn(_ptr(frame_scores), frame_scores.numel(), float(tau), int(block_idx),
+            qb.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), _stream_ptr(stream))
     if st < 0:
         raise SdvgError(st, "sdvg_worst_frame_route")
     return int(st), qb[0]
 
 
-def worst_frame_route_batch(frame_scores, tau, block_idx=None, first_block_idx=0, stream=None):
-    """sdvg_worst_frame_route_batch: frame_scores [n_blocks, n_frames] fp32; returns device
-    tensors (decisions int32 [n_blocks], q_b float32 [n_blocks]). Asynchronous."""
+def worst_frame_route_batch(frame_scores, tau, block_idx=None, first_block_idx=0, stream=None, mode="min"):
+    """sdvg_worst_frame_route_batch (mode "min") or sdvg_avg_frame_route_batch (mode "mean"):
+    frame_scores [n_blocks, n_frames] fp32; returns device tensors (decisions int32 [n_blocks],
+    q_b float32 [n_blocks]). Asynchronous."""
+    fn = {"min": lib().sdvg_worst_frame_route_batch, "mean": lib().sdvg_avg_frame_route_batch}[mode]
     _check_dev(frame_scores, block_idx)
     if frame_scores.dtype != torch.float32 or frame_scores.dim() != 2 or not frame_scores.is_contiguous():
         raise ValueError("frame_scores must be a dense 2-d float32 tensor")
@@ -193,9 +199,8 @@ def worst_frame_route_batch(frame_scores, tau, block_idx=None, first_block_idx=0
         raise ValueError("block_idx must be int32 [n_blocks]")
     dec = torch.empty(n_blocks, dtype=torch.int32, device=frame_scores.device)
     qb = torch.empty(n_blocks, dtype=torch.float32, device=frame_scores.device)
-    st = lib().sdvg_worst_frame_route_batch(_ptr(frame_scores), n_blocks, n_frames, float(tau),
-                                            _ptr(block_idx), int(first_block_idx), _ptr(dec),
-                                            _ptr(qb), _stream_ptr(stream))
+    st = fn(_ptr(frame_scores), n_blocks, n_frames, float(tau), _ptr(block_idx), int(first_block_idx),
+            _ptr(dec), _ptr(qb), _stream_ptr(stream))
     if st != 0:
         raise SdvgError(st, "sdvg_worst_frame_route_batch")
     return dec, qb

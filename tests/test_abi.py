@@ -127,10 +127,12 @@ def test_kv_rollback_argument_checks(P, new_len, expect):
     (FAKE, 12, -0.7, -1, -3), (FAKE + 2, 12, -0.7, 1, -4)])
 def test_route_rejects_bad_arguments(P, scores, n, tau, blk, expect):
     assert P.lib().sdvg_worst_frame_route(scores, n, tau, blk, None, None) == expect
+    assert P.lib().sdvg_avg_frame_route(scores, n, tau, blk, None, None) == expect
 
 
-def test_route_batch_rejects_bad_arguments(P):
-    f = P.lib().sdvg_worst_frame_route_batch
+@pytest.mark.parametrize("name", ["sdvg_worst_frame_route_batch", "sdvg_avg_frame_route_batch"])
+def test_route_batch_rejects_bad_arguments(P, name):
+    f = getattr(P.lib(), name)
     assert f(None, 4, 12, -0.7, None, 0, FAKE, None, None) == -1
     assert f(FAKE, 4, 12, -0.7, None, 0, None, None, None) == -1
     assert f(FAKE, 0, 12, -0.7, None, 0, FAKE, None, None) == -2

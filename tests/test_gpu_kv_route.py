@@ -168,6 +168,37 @@ def test_route_batch_matches_oracle_for_both_score_generators():
         assert dec2[0].item() == 0
 
 
+def test_avg_frame_route_matches_oracle():
+    """The ablation's average-frame router (fp64 sum in frame order), bit-exact, single and batched."""
+    import paper_2604_17397_amd as P
+
+    def gpu(scores, tau, b):
+        return P.worst_frame_route(torch.from_numpy(np.asarray(scores, np.float32)).cuda(), tau, b, mode="mean")
+
+    for F in (1, 3, 12, 65, 200):
+        for trial in range(3):
+            s = si.frame_scores_iid(90 + trial, 1, n_frames=F)[0]
+            for tau in (-0.5, -0.3, float(np.float32(s.astype(np.float64).mean()))):
+                for b in (0, 4):
+                    assert same_route(gpu(s, tau, b), oracle.route(s, tau, b, mode="mean")), (F, tau, b)
+    cases = [[16777216.0, 1.0, 1.0, -16777216.0], [0.5, 0.25, 0.25], [np.inf, 1.0], [np.inf, -np.inf],
+             [0.2, np.nan, 0.1], [-0.0, -0.0], [1e-45, 1e-45, 0.0], [3.4e38, 3.4e38]]
+    for c in cases:
+        for tau in (0.0, 0.5, -np.inf):
+            assert same_route(gpu(c, tau, 2), oracle.route(np.array(c, np.float32), tau, 2, mode="mean")), (c, tau)
+    n = 2048
+    scores = si.frame_scores_correlated(78, n)
+    idx = (np.arange(n) % 9).astype(np.int32)
+    for tau in (-0.5, -0.3):
+        dec, qb = P.worst_frame_route_batch(torch.from_numpy(scores).cuda(), tau,
+                                            block_idx=torch.from_numpy(idx).cuda(), mode="mean")
+        dec, qb = dec.cpu().numpy(), qb.cpu().numpy()
+        for i in range(n):
+            d, q = oracle.route(scores[i], tau, int(idx[i]), mode="mean")
+            assert d == dec[i] and q.view(np.uint32) == qb[i].view(np.uint32)
+        assert dec[idx == 0].sum() == 0
+
+
 def test_mfma_probe_runs():
     """The MFMA-only measurement kernel: runs, reports its FLOP count and a clock reading."""
     import paper_2604_17397_amd as P

@@ -181,3 +181,27 @@ def test_table1_ordering_property_holds_for_router():
     scores = si.frame_scores_correlated(7, 2000)
     ours = [np.mean([oracle.route(scores[i], t, 1 + i % 8)[0] for i in range(2000)]) for t in taus]
     assert ours == sorted(ours) and ours[-1] > ours[0]
+
+
+def test_mean_route_exact_values_and_closed_form_accept_probability():
+    # Sec. 4.3 "Min-frame vs. average-frame scoring": the ablation's router. Exact pins: means
+    # that are representable (or whose correctly rounded fp32 value is known), the accept rule
+    # and block 0; statistical pin: the mean of F i.i.d. N(mu, sigma) rewards is N(mu, sigma/sqrt(F)),
+    # so P(accept) = 1 - Phi((tau - mu) sqrt(F) / sigma).
+    dec, qb = oracle.route(np.array([1.0, 2.0, 3.0, 6.0], np.float32), 3.0, 1, mode="mean")
+    assert dec == 1 and qb == np.float32(3.0)
+    dec, qb = oracle.route(np.array([1.0, 2.0, 3.0, 6.0], np.float32), 3.0, 0, mode="mean")
+    assert dec == 0 and qb == np.float32(3.0)
+    dec, qb = oracle.route(np.array([0.5, 0.25, 0.25], np.float32), 0.3334, 2, mode="mean")
+    assert dec == 0 and qb.view(np.uint32) == np.float32(1.0 / 3.0).view(np.uint32)
+    # a sum that fp32 accumulation would get wrong: 2^24 + 1 + 1 - 2^24 = 2 exactly in fp64
+    dec, qb = oracle.route(np.array([16777216.0, 1.0, 1.0, -16777216.0], np.float32), 0.5, 1, mode="mean")
+    assert dec == 1 and qb == np.float32(0.5)
+    dec, qb = oracle.route(np.array([0.2, np.nan, 0.1], np.float32), -10.0, 1, mode="mean")
+    assert dec == 0 and qb.view(np.uint32) == 0x7FC00000
+    n = 60_000
+    scores = si.frame_scores_iid(43, n)
+    for tau in (-0.5, -0.3, -0.2):
+        p = 1 - 0.5 * (1 + math.erf((tau + 0.3) * math.sqrt(12) / 0.6 / math.sqrt(2)))
+        acc = sum(oracle.route(scores[i], tau, 1, mode="mean")[0] for i in range(0, n, 3)) / (n // 3)
+        assert abs(acc - p) < 4 * math.sqrt(p * (1 - p) / (n // 3)) + 1e-3
