@@ -155,6 +155,24 @@ def main():
         "accepted_blocks": int(accepted),
     }
 
+    # snapshot / restore of an opaque buffer (1 GiB), outside the step: a next-row kernel
+    snap_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    snap_dst = torch.empty_like(snap_src)
+    P.buffer_snapshot(snap_dst, snap_src)
+    torch.cuda.synchronize()
+    se = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    se[0].record()
+    for _ in range(5):
+        P.buffer_snapshot(snap_dst, snap_src)
+    se[1].record()
+    torch.cuda.synchronize()
+    snap_ms = se[0].elapsed_time(se[1]) / 5
+    snap_gbps = 2.0 * (1 << 30) / (snap_ms * 1e-3) / 1e9
+    line["hbm_kernels"]["buffer_snapshot"] = {"bound": "hbm", "achieved": round(snap_gbps, 1), "peak": PEAK_HBM_GBPS,
+                                              "unit": "GB/s", "frac": round(snap_gbps / PEAK_HBM_GBPS, 4),
+                                              "bytes": 2.0 * (1 << 30), "ms": round(snap_ms, 4)}
+    del snap_src, snap_dst
+
     # what the matrix cores of this chip deliver with nothing else going on, and at what clock
     P.probe_mfma(4000)
     torch.cuda.synchronize()

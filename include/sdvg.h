@@ -107,6 +107,17 @@ int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk, i
 int sdvg_kv_rollback(sdvg_kv_cache *cache, int64_t new_len, void *stream);
 
 /*
+ * Snapshot / restore of an opaque device buffer (paper Sec. 3 "Inference flow" and Sec. 4.1
+ * "Hardware and implementation": the VAE decode cache is cloned before a draft is scored and
+ * restored when the draft is rejected). One call copies n_bytes from src to dst; cloning is
+ * (snapshot <- live), restoring is (live <- snapshot). The library knows nothing of the contents.
+ *   dst, src  device, 16-byte aligned, caller-owned, must not overlap (SDVG_ERR_RANGE).
+ *   n_bytes   >= 0; 0 is a no-op that touches nothing (pointers may then be NULL).
+ * Bit-exact; bytes outside [dst, dst + n_bytes) are not written. Asynchronous on `stream`.
+ */
+int sdvg_buffer_snapshot(void *dst, const void *src, int64_t n_bytes, void *stream);
+
+/*
  * Worst-frame routing (paper Sec. 3 Eq. (1): q_b = min over the block's F decoded frames of
  * the per-frame reward; "Inference flow": accept iff q_b >= tau; "Force-reject the first
  * block": block 0 is always rejected, whatever its score).

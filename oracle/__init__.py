@@ -6,6 +6,7 @@ from .oracle import (  # noqa: F401
     block_attn,
     kv_commit,
     kv_rollback,
+    buffer_copy,
     route,
     num_threads,
     KVMirror,

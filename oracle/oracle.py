@@ -32,6 +32,8 @@ def _lib():
         lib.sdvg_oracle_kv_rollback.restype = ctypes.c_int
         lib.sdvg_oracle_kv_rollback.argtypes = [vp, vp, i64, i64, i64, i64,
                                                 ctypes.POINTER(i64), i64]
+        lib.sdvg_oracle_buffer_copy.restype = ctypes.c_int
+        lib.sdvg_oracle_buffer_copy.argtypes = [vp, vp, i64]
         lib.sdvg_oracle_route.restype = ctypes.c_int
         lib.sdvg_oracle_route.argtypes = [vp, i64, ctypes.c_float, i64, ctypes.c_int, vp]
         lib.sdvg_oracle_num_threads.restype = ctypes.c_int
@@ -132,6 +134,16 @@ def kv_rollback(mirror, new_len):
                                         ctypes.byref(n), int(new_len))
     mirror.cache_len = int(n.value)
     return rc
+
+
+def buffer_copy(dst, src, n_bytes=None):
+    """dst[:n_bytes] = src[:n_bytes] on two contiguous uint8 arrays, in place; returns the C status."""
+    assert dst.dtype == np.uint8 and src.dtype == np.uint8
+    assert dst.flags.c_contiguous and src.flags.c_contiguous
+    if n_bytes is None:
+        n_bytes = src.size
+    assert n_bytes <= dst.size and n_bytes <= src.size
+    return _lib().sdvg_oracle_buffer_copy(dst.ctypes.data, src.ctypes.data, int(n_bytes))
 
 
 def route(scores, tau, block_idx, mode="min"):

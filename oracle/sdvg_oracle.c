@@ -12,7 +12,10 @@
  *   - KV commit / rollback: Sec. 3 "Inference flow" (accepted draft is committed to the
  *     target's KV cache; on reject the cache must look as if the draft was never there).
  *   - worst-frame routing: Sec. 3 Eq. (1) (min over frames), the accept rule q_b >= tau of
- *     "Inference flow", and "Force-reject the first block".
+ *     "Inference flow", and "Force-reject the first block"; mode 1 is the average-frame variant
+ *     of the ablation (Sec. 4.3 "Min-frame vs. average-frame scoring").
+ *   - snapshot / restore of an opaque buffer: Sec. 3 "Inference flow" (VAE decode cache cloned
+ *     before scoring, restored on rejection): a byte copy.
  *
  * Everything is fp64, two-pass, materialised-row: deliberately NOT tiled / online.
  * Element types: 0 = bfloat16 bit patterns (uint16), 1 = float32. Both widen exactly to fp64.
@@ -202,6 +205,16 @@ int sdvg_oracle_route(const float *scores, int64_t n_frames, float tau, int64_t 
   }
   if (q_b_out) *q_b_out = qb;
   return (block_idx != 0 && qb >= tau) ? 1 : 0;
+}
+
+/*
+ * Snapshot / restore of an opaque buffer (paper Sec. 3 "Inference flow": the VAE decode cache is
+ * cloned before draft scoring and restored on rejection): dst[i] = src[i], byte by byte.
+ */
+int sdvg_oracle_buffer_copy(uint8_t *dst, const uint8_t *src, int64_t n_bytes) {
+  if (n_bytes < 0) return -2;
+  for (int64_t i = 0; i < n_bytes; ++i) dst[i] = src[i];
+  return 0;
 }
 
 /* Threads the attention loop above will use (reported beside the timed baseline). */

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     block_attn,
     kv_commit,
     kv_rollback,
+    buffer_snapshot,
     worst_frame_route,
     worst_frame_route_batch,
     probe_mfma,

@@ -63,6 +63,8 @@ def lib():
         L.sdvg_worst_frame_route.argtypes = [vp, i32, f32, i32, ctypes.POINTER(f32), vp]
         L.sdvg_worst_frame_route_batch.restype = ctypes.c_int
         L.sdvg_worst_frame_route_batch.argtypes = [vp, i32, i32, f32, vp, i32, vp, vp, vp]
+        L.sdvg_buffer_snapshot.restype = ctypes.c_int
+        L.sdvg_buffer_snapshot.argtypes = [vp, vp, i64, vp]
         L.sdvg_avg_frame_route.restype = ctypes.c_int
         L.sdvg_avg_frame_route.argtypes = [vp, i32, f32, i32, ctypes.POINTER(f32), vp]
         L.sdvg_avg_frame_route_batch.restype = ctypes.c_int
@@ -168,6 +170,21 @@ def kv_rollback(cache, new_len, stream=None):
     st = lib().sdvg_kv_rollback(ctypes.byref(cache.c), int(new_len), _stream_ptr(stream))
     if st != 0:
         raise SdvgError(st, "sdvg_kv_rollback")
+
+
+def buffer_snapshot(dst, src, n_bytes=None, stream=None):
+    """sdvg_buffer_snapshot: dst[:n_bytes] = src[:n_bytes] for two device tensors viewed as bytes
+    (n_bytes defaults to the size of src)."""
+    _check_dev(dst, src)
+    if not (dst.is_contiguous() and src.is_contiguous()):
+        raise ValueError("buffer_snapshot needs contiguous tensors")
+    if n_bytes is None:
+        n_bytes = src.numel() * src.element_size()
+    if n_bytes > dst.numel() * dst.element_size() or n_bytes > src.numel() * src.element_size():
+        raise ValueError("n_bytes exceeds a buffer")
+    st = lib().sdvg_buffer_snapshot(_ptr(dst), _ptr(src), int(n_bytes), _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_buffer_snapshot")
 
 
 def worst_frame_route(frame_scores, tau, block_idx, stream=None, mode="min"):

@@ -77,6 +77,21 @@ __global__ __launch_bounds__(kThreads) void kv_zero_strided_kernel(uint16_t *__r
     *reinterpret_cast<u32x4 *>(dst + dst_offset(m, g)) = zero;
 }
 
+// Plain device-to-device copy of an opaque buffer: 16-byte chunks, one per thread; the thread
+// after the last full chunk moves the 0-15 tail bytes.
+__global__ __launch_bounds__(kThreads) void buffer_copy_kernel(const u32x4 *__restrict__ src,
+                                                               u32x4 *__restrict__ dst, int64_t chunks,
+                                                               int tail_bytes) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i < chunks) {
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+  } else if (i == chunks) {
+    const uint8_t *sb = reinterpret_cast<const uint8_t *>(src + chunks);
+    uint8_t *db = reinterpret_cast<uint8_t *>(dst + chunks);
+    for (int b = 0; b < tail_bytes; ++b) db[b] = sb[b];
+  }
+}
+
 int validate_cache(const sdvg_kv_cache *c) {
   if (!c) return SDVG_ERR_NULL;
   if (!c->k || !c->v) return SDVG_ERR_NULL;
@@ -156,5 +171,23 @@ extern "C" int sdvg_kv_rollback(sdvg_kv_cache *cache, int64_t new_len, void *str
   }
   SDVG_HIP_CHECK(hipGetLastError());
   cache->cache_len = new_len;
+  return SDVG_OK;
+}
+
+extern "C" int sdvg_buffer_snapshot(void *dst, const void *src, int64_t n_bytes, void *stream) {
+  if (n_bytes < 0) return SDVG_ERR_SHAPE;
+  if (n_bytes == 0) return SDVG_OK;
+  if (!dst || !src) return SDVG_ERR_NULL;
+  if (!sdvg::aligned16(dst) || !sdvg::aligned16(src)) return SDVG_ERR_ALIGN;
+  const uintptr_t d = reinterpret_cast<uintptr_t>(dst), c = reinterpret_cast<uintptr_t>(src);
+  if (d < c + static_cast<uintptr_t>(n_bytes) && c < d + static_cast<uintptr_t>(n_bytes)) return SDVG_ERR_RANGE;
+  const int64_t chunks = n_bytes / 16;
+  const int tail = static_cast<int>(n_bytes % 16);
+  const int64_t blocks = (chunks + 1 + kThreads - 1) / kThreads;
+  if (blocks > 0x7FFFFFFF) return SDVG_ERR_UNSUPPORTED;  // more than 8 TiB
+  hipLaunchKernelGGL(buffer_copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const u32x4 *>(src),
+                     static_cast<u32x4 *>(dst), chunks, tail);
+  SDVG_HIP_CHECK(hipGetLastError());
   return SDVG_OK;
 }

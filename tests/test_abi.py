@@ -141,6 +141,18 @@ def test_route_batch_rejects_bad_arguments(P, name):
     assert f(FAKE, 4, 12, -0.7, None, -2, FAKE, None, None) == -3
 
 
+def test_buffer_snapshot_rejects_bad_arguments(P):
+    f = P.lib().sdvg_buffer_snapshot
+    assert f(None, None, 0, None) == 0                 # empty copy: nothing to do
+    assert f(FAKE, FAKE + 4096, -1, None) == -2
+    assert f(None, FAKE, 16, None) == -1
+    assert f(FAKE, None, 16, None) == -1
+    assert f(FAKE + 8, FAKE + 4096, 16, None) == -4
+    assert f(FAKE, FAKE + 4096 + 4, 16, None) == -4
+    assert f(FAKE, FAKE + 16, 32, None) == -3          # overlapping ranges
+    assert f(FAKE + 16, FAKE, 32, None) == -3
+
+
 def test_missing_library_fails_loudly(P, monkeypatch):
     import paper_2604_17397_amd.binding as b
     monkeypatch.setattr(b, "_LIB", None)

@@ -205,3 +205,24 @@ def test_mean_route_exact_values_and_closed_form_accept_probability():
         p = 1 - 0.5 * (1 + math.erf((tau + 0.3) * math.sqrt(12) / 0.6 / math.sqrt(2)))
         acc = sum(oracle.route(scores[i], tau, 1, mode="mean")[0] for i in range(0, n, 3)) / (n // 3)
         assert abs(acc - p) < 4 * math.sqrt(p * (1 - p) / (n // 3)) + 1e-3
+
+
+def test_buffer_copy_is_a_byte_copy_and_touches_nothing_else():
+    # Sec. 3 "Inference flow": clone before scoring, restore on rejection. Pins: the copy equals
+    # numpy's own slice assignment, leaves the bytes around it alone, and clone -> mutate ->
+    # restore returns the original bytes.
+    rng = np.random.default_rng(5)
+    for n in (0, 1, 15, 16, 17, 4099):
+        src = rng.integers(0, 256, n + 7, dtype=np.uint8)
+        dst = np.full(n + 9, 0xA5, np.uint8)
+        want = dst.copy()
+        want[:n] = src[:n]
+        assert oracle.buffer_copy(dst, src, n) == 0
+        assert np.array_equal(dst, want)
+    live = rng.integers(0, 256, 1000, dtype=np.uint8)
+    orig = live.copy()
+    snap = np.zeros_like(live)
+    oracle.buffer_copy(snap, live)
+    live[::3] ^= 0xFF
+    oracle.buffer_copy(live, snap)
+    assert np.array_equal(live, orig)
