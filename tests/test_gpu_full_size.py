@@ -60,6 +60,12 @@ def test_target_shape_cache_sweep_four_heads(k):
     attn_case(40, k * T, seed=200 + k, heads=[0, 13, 26, 39], rows=si.parity_rows(T)[::3])
 
 
+def test_target_shape_nine_block_protocol():
+    # The paper's protocol generates 9 blocks per video (Sec. 4.1): the last block attends over
+    # 8 cached blocks, 4680 queries x 42120 keys. Four heads on a thinned row sample.
+    attn_case(40, 8 * T, seed=208, heads=[0, 13, 26, 39], rows=si.parity_rows(T)[::3])
+
+
 def test_speculative_round_at_target_shape():
     """40 layers x 40 heads, 5 cached blocks, draft staged in slot 5, routed, kept or rolled back.
     Three layers are compared in full against the oracle mirror; every layer is compared on
