@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--workload", default="target", choices=["target", "drafter", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--denoise-steps", type=int, default=4)
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time attention at 0..8 cached blocks (adds launches of other shapes)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by heads with no exchange "
@@ -156,22 +158,23 @@ def main():
     }
 
     # attention rate against the cache length, up to the paper's 9-block protocol (8 cached blocks)
-    sw_k = si.device_normal_bf16((8 * T, H, D), si.SEED, si.TID_K_CACHE + 50, device=dev)
-    sw_v = si.device_normal_bf16((8 * T, H, D), si.SEED, si.TID_V_CACHE + 50, device=dev)
-    sweep = []
-    for kb_ in range(9):
-        c_ = kb_ * T
-        P.block_attn(q, sw_k, sw_v, k_blk[0], v_blk[0], c_, out=out)
-        torch.cuda.synchronize()
-        we = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        we[0].record()
-        for _ in range(10):
+    if args.sweep:
+        sw_k = si.device_normal_bf16((8 * T, H, D), si.SEED, si.TID_K_CACHE + 50, device=dev)
+        sw_v = si.device_normal_bf16((8 * T, H, D), si.SEED, si.TID_V_CACHE + 50, device=dev)
+        sweep = []
+        for kb_ in range(9):
+            c_ = kb_ * T
             P.block_attn(q, sw_k, sw_v, k_blk[0], v_blk[0], c_, out=out)
-        we[1].record()
-        torch.cuda.synchronize()
-        sweep.append(round(si.attn_flops(T, c_ + T, H, D) / (we[0].elapsed_time(we[1]) / 10 * 1e-3) / 1e12, 1))
-    line["roofline"]["tflops_by_cached_blocks_0_to_8"] = sweep
-    del sw_k, sw_v
+            torch.cuda.synchronize()
+            we = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            we[0].record()
+            for _ in range(10):
+                P.block_attn(q, sw_k, sw_v, k_blk[0], v_blk[0], c_, out=out)
+            we[1].record()
+            torch.cuda.synchronize()
+            sweep.append(round(si.attn_flops(T, c_ + T, H, D) / (we[0].elapsed_time(we[1]) / 10 * 1e-3) / 1e12, 1))
+        line["roofline"]["tflops_by_cached_blocks_0_to_8"] = sweep
+        del sw_k, sw_v
 
     # snapshot / restore of an opaque buffer (1 GiB), outside the step: a next-row kernel
     snap_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

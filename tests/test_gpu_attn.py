@@ -94,3 +94,70 @@ def test_f32_check_jittered_heads():
 @pytest.mark.parametrize("cache_len,n_blk,n_q", [(0, 72, 72), (1, 5, 3), (31, 33, 33), (32, 64, 1), (100, 129, 129)])
 def test_f32_check_seam_and_tails(cache_len, n_blk, n_q):
     run_case_f32(2, n_blk, cache_len, seed=3 + cache_len, cap_extra=2, n_q=n_q)
+
+
+# ---------------------------------------------------------------- lazy running maximum
+
+def structured_case(pattern, n_k_total=700, n_q=70, H=2, amp=40.0, scale=None):
+    """Scores with a designed profile along the keys: q = one direction u per row (with a row
+    dependent gain), k_j = g(j) * u, so that s_ij ~ gain_i * g(j) * |u|^2 * scale. `pattern`
+    picks g: rising (the running maximum must be raised again and again, by far more than the
+    kernel's 2^20 overflow limit in total), falling (tile 0 holds the maximum, later
+    probabilities underflow), spike_last (one huge logit in the ragged last tile), flat."""
+    import paper_2604_17397_amd as P
+    rng = np.random.default_rng(11)
+    d = 128
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    j = np.arange(n_k_total, dtype=np.float64)
+    g = {"rising": amp * j / n_k_total, "falling": amp * (1.0 - j / n_k_total),
+         "spike_last": np.where(j == n_k_total - 1, amp, 0.1), "flat": np.full(n_k_total, 0.5)}[pattern]
+    gain = np.linspace(0.5, 2.0, n_q) * math_sqrt(d)
+    q = np.einsum("i,d->id", gain, u)[:, None, :].repeat(H, axis=1)
+    k = np.einsum("j,d->jd", g, u)[:, None, :].repeat(H, axis=1)
+    k += 0.01 * rng.standard_normal(k.shape)
+    v = rng.standard_normal((n_k_total, H, d))
+    c_len = 333
+    bits = lambda a: si.f32_to_bf16_bits(a.astype(np.float32))
+    qb, kb_all, vb_all = bits(q), bits(k), bits(v)
+    kc, kblk, vc, vblk = kb_all[:c_len], kb_all[c_len:], vb_all[:c_len], vb_all[c_len:]
+    out = torch.full((n_q, H, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.block_attn(to_dev_bf16(qb), to_dev_bf16(kc), to_dev_bf16(vc), to_dev_bf16(kblk), to_dev_bf16(vblk),
+                 c_len, out=out, scale=scale)
+    torch.cuda.synchronize()
+    ref = oracle.block_attn(qb, kc, vc, kblk, vblk, c_len, scale=scale)
+    return attn_errors(bits_of(out), ref)
+
+
+def math_sqrt(x):
+    import math
+    return math.sqrt(x)
+
+
+@pytest.mark.parametrize("pattern", ["rising", "falling", "spike_last", "flat"])
+@pytest.mark.parametrize("amp", [8.0, 40.0, 150.0])
+def test_score_profiles_that_move_the_running_maximum(pattern, amp):
+    # amp = 150 gives logits whose exponentials span far more than fp32 can hold relative to
+    # tile 0: without a raised maximum the probabilities overflow, with a wrong rescale the
+    # output is visibly off.
+    check(structured_case(pattern, amp=amp))
+
+
+def test_softmax_scale_argument():
+    check(structured_case("rising", amp=20.0, scale=0.05))
+    check(structured_case("flat", scale=0.3))
+
+
+def test_head_major_strides():
+    """q / out / k / v given as [heads, tokens, 128] memory viewed as [tokens, heads, 128]."""
+    import paper_2604_17397_amd as P
+    H, n_blk, c_len = 3, 150, 200
+    q, kc, vc, kb, vb = si.attn_inputs(H, n_blk, c_len, seed=31)
+    hm = lambda a: to_dev_bf16(np.ascontiguousarray(a.transpose(1, 0, 2))).transpose(0, 1)
+    dq, dkc, dvc, dkb, dvb = hm(q), hm(kc), hm(vc), hm(kb), hm(vb)
+    out = torch.full((H, n_blk, 128), float("nan"), dtype=torch.bfloat16, device="cuda").transpose(0, 1)
+    assert dq.stride() == (128, n_blk * 128, 1)
+    P.block_attn(dq, dkc, dvc, dkb, dvb, c_len, out=out)
+    torch.cuda.synchronize()
+    ref = oracle.block_attn(q, kc, vc, kb, vb, c_len)
+    check(attn_errors(bits_of(out), ref))
