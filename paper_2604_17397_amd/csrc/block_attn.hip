@@ -423,9 +423,8 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     t_evt = next_event(t + 1);
   };
 
-  // One tile: vector phase (softmax of the shifted S(t)), barrier, matrix phase (copies of tile
-  // t+3 started, S(t+1) = K(t+1) Q^T, then O += P(t) V(t) with S(t+1) shifted on the side),
-  // barrier. R = t % 4, the ring slot of tile t, is a compile-time constant: the loop is
+  // One tile: vector phase (softmax of S(t)), barrier, matrix phase (copies of tile t+3 started
+  // between the MFMA groups, S(t+1) = K(t+1) Q^T, then O += P(t) V(t)), barrier. R = t % 4, the ring slot of tile t, is a compile-time constant: the loop is
   // unrolled by 4 and every LDS address is a base register plus an immediate.
   // The last tile computes a meaningless S(t+1) from a stale slot; nothing reads it.
   auto tile_body = [&](auto slot, int t) __attribute__((always_inline)) {
