@@ -119,7 +119,8 @@ def main():
     t1 = time.perf_counter()
 
     ms_step = (t1 - t0) * 1e3 / args.steps
-    attn_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / (args.steps * S * L)
+    per_step_attn = sorted(e[0].elapsed_time(e[1]) / (S * L) for e in evs)
+    attn_ms = sum(per_step_attn) / args.steps
     route_us = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps * 1e3
     commit_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
     rollback_ms = sum(e[3].elapsed_time(e[4]) for e in evs) / args.steps
@@ -143,7 +144,9 @@ def main():
                      "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": TRAFFIC_TARGET["block_attn"] if args.workload == "target" else None,
-                     "avg_launch_ms": round(attn_ms, 4)},
+                     "avg_launch_ms": round(attn_ms, 4),
+                     "median_launch_ms": round(per_step_attn[len(per_step_attn) // 2], 4),
+                     "min_launch_ms": round(per_step_attn[0], 4)},
         "hbm_kernels": {
             "kv_commit": {"bound": "hbm", "achieved": round(commit_gbps, 1), "peak": PEAK_HBM_GBPS,
                           "unit": "GB/s", "frac": round(commit_gbps / PEAK_HBM_GBPS, 4),
