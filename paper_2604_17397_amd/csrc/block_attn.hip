@@ -347,12 +347,20 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
         pb[kb][i] = __builtin_convertvector(pp, bf16x2);
       }
     __builtin_amdgcn_sched_barrier(0);
-    float dl[4] = {0.f, 0.f, 0.f, 0.f};
+    float dl[4];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        dl[i & 3] = __builtin_amdgcn_fdot2_f32_bf16(pb[kb][i], ones, dl[i & 3], false);
+        if (kb == 0 && i < 4) {
+          // first use of the accumulator: three-operand form with a zero addend (the builtin
+          // would spend a v_mov on zeroing the register of the accumulating form)
+          uint32_t pbits;
+          __builtin_memcpy(&pbits, &pb[kb][i], 4);
+          asm("v_dot2_f32_bf16 %0, %1, %2, 0" : "=v"(dl[i & 3]) : "v"(pbits), "s"(0x3f803f80u));
+        } else {
+          dl[i & 3] = __builtin_amdgcn_fdot2_f32_bf16(pb[kb][i], ones, dl[i & 3], false);
+        }
         pf[kb * 2 + (i >> 2)][(i & 3) * 2] = pb[kb][i][0];
         pf[kb * 2 + (i >> 2)][(i & 3) * 2 + 1] = pb[kb][i][1];
       }
