@@ -20,7 +20,8 @@
 //   half an iteration apart, so that on every SIMD one wave is in its matrix phase (S of the
 //   next tile, then PV of the current one: 32 MFMAs) while the other is in its vector phase
 //   (softmax of its tile). Workgroup barriers between the phases keep the groups in lockstep.
-//   Softmax is in the log2 domain with a lazy running maximum (see softmax_tile below).
+//   Softmax is in the log2 domain with a lazy running maximum whose negative is carried in the
+//   initial value of the score accumulators (see softmax_tile below).
 #include <math.h>
 #include <stdlib.h>
 
@@ -74,7 +75,7 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr) {
       "global_load_lds_dwordx4 %1, off"
       :
       : "s"(lds_addr), "v"(gptr)
-      : "memory");
+      : "memory", "m0");
 }
 // Same copy with the 64-token pointer step folded in: the 64-bit add sits between the M0 write
 // and the copy (covering the wait state M0 needs) and the stepped pointer is returned.
@@ -85,7 +86,7 @@ __device__ __forceinline__ const char *dma16_step(const char *gptr, uint64_t ste
       "global_load_lds_dwordx4 %0, off"
       : "+v"(gptr)
       : "s"(lds_addr), "s"(step)
-      : "memory");
+      : "memory", "m0");
   return gptr;
 }
 
@@ -215,13 +216,20 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   for (int u = 0; u < 4; ++u)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o_acc[u][i] = 0.f;
-  float m_run = -INFINITY;
   float l_run = 0.f;
   f32x16 s_acc[2];
   bf16x8 pf[4];
   bf16x8 fa[4], fb[4];  // two groups of 4 MFMA A-operands: one in use, one being fetched
-  const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // Minus the running maximum, in score units (before the softmax scale), and the same value in
+  // all 16 registers of a score accumulator: every QK^T chain starts from it, so the scores
+  // come out of the matrix cores already shifted and the softmax needs one multiply per score.
+  float s_shift = 0.f;
+  f32x16 s_init = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto set_shift = [&](float v) __attribute__((always_inline)) {
+    s_shift = v;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_init[i] = v;
+  };
 
   // One V^T operand: 16 keys (step j) x dim block u, two transposing reads.
   auto read_v = [&](bf16x8 &f, int slot, int j, int u) __attribute__((always_inline)) {
@@ -242,7 +250,7 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     o_acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[j], o_acc[u], 0, 0, 0);
   };
   auto mfma_k = [&](const bf16x8 &f, int s, int kb) __attribute__((always_inline)) {
-    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[s], s == 0 ? zero16 : s_acc[kb], 0, 0, 0);
+    s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[s], s == 0 ? s_init : s_acc[kb], 0, 0, 0);
   };
 #define SDVG_SB() __builtin_amdgcn_sched_barrier(0)
   // s_waitcnt lgkmcnt(0) alone: every LDS read issued so far has returned
@@ -261,9 +269,11 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   // QK group g; K group g+1 (or, after the last group, V group 0 of slot vslot) goes into `nxt`.
   // Half of the next group's reads are issued before this group's first MFMA (the matrix pipe
   // is still busy with the previous group's last one), the other half right after it, so every
-  // operand has at least three MFMA times to arrive.
-  auto qk_group = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int kslot, int g, int vslot)
-      __attribute__((always_inline)) {
+  // operand has at least three MFMA times to arrive. Copy number g of the tile three ahead
+  // (ring slot cp_slot, 64-token step cp_step) is started behind the second MFMA: no gap between
+  // two MFMAs then holds more than three other instructions, which the 32 cycles of an MFMA hide.
+  auto qk_group = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int kslot, int g, int vslot,
+                      int cp_slot = -1, uint64_t cp_step = 0) __attribute__((always_inline)) {
     SDVG_SB();
     if (g < 3) {
       read_k(nxt[0], kslot, 2 * g + 2, 0);
@@ -286,6 +296,9 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     }
     SDVG_SB();
     mfma_k(cur[1], 2 * g, 1);
+    SDVG_SB();
+    if (cp_slot >= 0) step_copy(cp_slot, g, cp_step);
+    SDVG_SB();
     mfma_k(cur[2], 2 * g + 1, 0);
     mfma_k(cur[3], 2 * g + 1, 1);
     SDVG_SB();
@@ -315,23 +328,27 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     SDVG_SB();
   };
 
-  // Vector phase: P^T = exp2(S^T * scale*log2e - m) rounded to bf16 in B-operand order, plus
+  // Vector phase: P^T = exp2(scale*log2e * (S^T - m)) rounded to bf16 in B-operand order, plus
   // this lane's share of the row sum, taken over the ROUNDED probabilities so that numerator
-  // and denominator of the softmax use the same weights.
-  // No maximum is computed on the fast path: the running maximum m may lag the true one, which
-  // changes nothing (both sides carry the same factor 2^-m) as long as exp2 stays in range.
-  // Only if the tile's sum of P comes out huge (a logit more than ~15 above m in log2 units)
-  // does the wave take the slow path: raise m to the true maximum, rescale O and l, form P again.
-  // The wave issues in order and is alone on the vector ALU during this phase, so the work is
-  // laid out in stages over all 32 scores (shift, exp2, convert, sum with four accumulators):
-  // no instruction depends on one issued just before it.
+  // and denominator of the softmax use the same weights. The shift by the running maximum m is
+  // already in the scores (s_init), so forming P costs one multiply and one exp2 per score.
+  // No maximum is computed on the fast path: m may lag the true maximum, which changes nothing
+  // (both sides carry the same factor) as long as exp2 stays in range. Only if the tile's sum
+  // of P comes out huge (a logit more than ~15 above m in log2 units) does the wave take the
+  // slow path: raise m to the true maximum, rescale O and l, form P again.
+  // The row sum unpacks the rounded pairs again (a shift and a mask) and adds them as fp32:
+  // four plain instructions per pair. The one-instruction alternative, v_dot2_f32_bf16 with a
+  // vector of ones, shares the matrix pipe with the partner wave's MFMAs and, queued behind
+  // them at lower priority, made the vector phase the longer of the two (measured: 16 of them
+  // per tile cost 250 cycles per phase; the 64 plain instructions that replace them cost none).
+  // The work is laid out in stages over all 32 scores (scale, exp2, convert, sum on four
+  // accumulators): no instruction depends on one issued just before it.
   auto form_p = [&]() __attribute__((always_inline)) -> float {
     float pexp[2][16];
-    const float neg_m = -m_run;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) pexp[kb][i] = __builtin_fmaf(s_acc[kb][i], p.scale_log2e, neg_m);
+      for (int i = 0; i < 16; ++i) pexp[kb][i] = s_acc[kb][i] * p.scale_log2e;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -352,14 +369,15 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        if (kb == 0 && i < 4) {
-          // first use of the accumulator: three-operand form with a zero addend (the builtin
-          // would spend a v_mov on zeroing the register of the accumulating form)
-          uint32_t pbits;
-          __builtin_memcpy(&pbits, &pb[kb][i], 4);
-          asm("v_dot2_f32_bf16 %0, %1, %2, 0" : "=v"(dl[i & 3]) : "v"(pbits), "s"(0x3f803f80u));
+        uint32_t pbits;
+        __builtin_memcpy(&pbits, &pb[kb][i], 4);
+        const float lo = __uint_as_float(pbits << 16), hi = __uint_as_float(pbits & 0xffff0000u);
+        if (kb == 0 && i < 2) {
+          dl[2 * i] = lo;
+          dl[2 * i + 1] = hi;
         } else {
-          dl[i & 3] = __builtin_amdgcn_fdot2_f32_bf16(pb[kb][i], ones, dl[i & 3], false);
+          dl[(2 * i) & 3] += lo;
+          dl[(2 * i + 1) & 3] += hi;
         }
         pf[kb * 2 + (i >> 2)][(i & 3) * 2] = pb[kb][i][0];
         pf[kb * 2 + (i >> 2)][(i & 3) * 2 + 1] = pb[kb][i][1];
@@ -367,6 +385,7 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     __builtin_amdgcn_sched_barrier(0);
     return (dl[0] + dl[1]) + (dl[2] + dl[3]);
   };
+  // Largest score of the tile for this lane's query (both half-waves), relative to the shift.
   auto tile_max = [&]() __attribute__((always_inline)) -> float {
     float m4[4];
 #pragma unroll
@@ -377,17 +396,25 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
       for (int i = 4; i < 16; ++i) m4[i & 3] = fmaxf(m4[i & 3], s_acc[kb][i]);
     return lane_max32(fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3])));
   };
+  // Moves the running maximum up by d (score units, >= 0): the scores in hand and every later
+  // accumulator start d lower, and what has been summed so far shrinks by 2^(-d * scale*log2e).
+  auto raise_max = [&](float d) __attribute__((always_inline)) {
+    const float alpha = __builtin_amdgcn_exp2f(-d * p.scale_log2e);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o_acc[u][i] *= alpha;
+    l_run *= alpha;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_acc[kb][i] -= d;
+    set_shift(s_shift - d);
+  };
   auto softmax_tile = [&]() __attribute__((always_inline)) {
     float dl = form_p();
     if (__builtin_amdgcn_ballot_w64(!(dl < kPSumLimit)) != 0) {
-      const float m_new = fmaxf(m_run, tile_max() * p.scale_log2e);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o_acc[u][i] *= alpha;
-      l_run *= alpha;
-      m_run = m_new;
+      raise_max(fmaxf(tile_max(), 0.f));
       dl = form_p();
     }
     l_run += dl;
@@ -453,16 +480,11 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     wg_barrier();
     __builtin_amdgcn_s_setprio(1);
     if (__builtin_expect(t == t_evt, 0)) on_event(t);
-    // After each of the first four MFMA groups one copy of tile t+3 is started: the matrix
-    // pipe is still busy with the group's last MFMA, so these few instructions cost nothing.
-    qk_group(fa, fb, Rn, 0, R);
-    step_copy(Rp, 0, fast_step);
-    qk_group(fb, fa, Rn, 1, R);
-    step_copy(Rp, 1, fast_step);
-    qk_group(fa, fb, Rn, 2, R);
-    step_copy(Rp, 2, fast_step);
-    qk_group(fb, fa, Rn, 3, R);  // leaves V group 0 in fa
-    step_copy(Rp, 3, fast_step);
+    // Each of the four QK groups also starts one of the four copies of tile t+3.
+    qk_group(fa, fb, Rn, 0, R, Rp, fast_step);
+    qk_group(fb, fa, Rn, 1, R, Rp, fast_step);
+    qk_group(fa, fb, Rn, 2, R, Rp, fast_step);
+    qk_group(fb, fa, Rn, 3, R, Rp, fast_step);  // leaves V group 0 in fa
     if (__builtin_expect(mask_next, 0)) mask_tail(t + 1);
     pv_group(fa, fb, R, 0);
     pv_group(fb, fa, R, 1);
@@ -512,7 +534,14 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   qk_group(fb, fa, 0, 3, 0);  // (its V read is harmless: slot 0 holds V(0))
   wait_lds0();
   if (n_tiles == 1) mask_tail(0);
-  m_run = tile_max() * p.scale_log2e;  // the running maximum starts at tile 0's true maximum
+  {  // the running maximum starts at tile 0's true maximum
+    const float mx = tile_max();
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_acc[kb][i] -= mx;
+    set_shift(-mx);
+  }
   if (group_b) wg_barrier();  // group B runs one phase behind group A
 
   for (int t = 0;;) {
