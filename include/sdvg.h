@@ -60,7 +60,7 @@ typedef struct {
   int64_t o_token_stride, o_head_stride;     /* out */
   int64_t kv_token_stride, kv_head_stride;   /* k_cache, v_cache (one layer) */
   int64_t blk_token_stride, blk_head_stride; /* k_blk, v_blk */
-  float scale;      /* softmax scale, 1/sqrt(head_dim) in the paper's models */
+  float scale;      /* softmax scale; 0 selects 1/sqrt(head_dim), the paper's models' value */
   int32_t dtype;    /* SDVG_BF16: all tensors bf16. SDVG_F32: all tensors fp32 (check path) */
 } sdvg_attn_desc;
 
@@ -79,8 +79,12 @@ typedef struct {
  *   Arithmetic (bf16): products on the matrix cores with fp32 accumulation, fp32 softmax
  *   statistics, probabilities rounded to bf16 before the PV product (the row sum is taken over
  *   the rounded values), bf16 output (RNE). SDVG_F32 is a slow all-fp32 check path.
- *   scale must be finite and > 0, else SDVG_ERR_RANGE. Inputs are assumed finite.
- * Asynchronous: enqueued on `stream`; returns SDVG_OK or a negative status.
+ *   scale must be finite and >= 0 (0 = 1/sqrt(head_dim)), else SDVG_ERR_RANGE. Inputs are
+ *   assumed finite.
+ * Asynchronous: enqueued on `stream`; returns SDVG_OK or a negative status. The call only
+ * launches a kernel, so it may be recorded into a HIP graph -- but the first SDVG_BF16 call on
+ * a device also raises that kernel's dynamic-LDS limit (once per device, thread-safe), which
+ * is not a capturable operation: make one eager call on the device before capturing.
  */
 int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cache,
                     const void *v_cache, const void *k_blk, const void *v_blk,
@@ -92,7 +96,11 @@ int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cac
  * unconditionally). Copies k_blk, v_blk -- device, dense [n_layers][T][n_heads][128] bf16 --
  * into tokens [slot*T, (slot+1)*T) of every layer, then sets cache->cache_len = (slot+1)*T.
  * Append-only: requires slot*T == cache->cache_len and (slot+1)*T <= capacity_tokens, else
- * SDVG_ERR_RANGE. One launch covers all layers. Asynchronous on `stream`.
+ * SDVG_ERR_RANGE. k_blk / v_blk must not overlap the destination slot of any layer
+ * (SDVG_ERR_RANGE). The descriptor's strides must keep rows and layers apart: the larger of
+ * token_stride and head_stride steps over everything the smaller one spans, and layer_stride
+ * over a whole layer (SDVG_ERR_SHAPE otherwise; the same check guards sdvg_kv_rollback).
+ * One launch covers all layers. Asynchronous on `stream`.
  */
 int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk, int32_t slot,
                    void *stream);

@@ -4,7 +4,6 @@ PyTorch tensors supply device memory (`data_ptr()`) and the HIP stream; nothing 
 here and there is no fallback: a missing library raises.
 """
 import ctypes
-import math
 import os
 
 import torch
@@ -123,7 +122,9 @@ class KVCache:
 
 def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=None, stream=None):
     """sdvg_block_attn: q, k_blk, v_blk [tokens, heads, 128]; k_cache, v_cache one layer's
-    [>= cache_len, heads, 128] (may be None when cache_len == 0). Returns out."""
+    [>= cache_len, heads, 128] (may be None when cache_len == 0). `scale=None` passes 0, which the
+    library reads as 1/sqrt(head_dim). Returns out. Shapes are checked against each other here,
+    because a wrong length or head count would make the kernel read outside the tensors."""
     _check_dev(q, k_cache, v_cache, k_blk, v_blk, out)
     if q.dtype == torch.bfloat16:
         dtype = SDVG_BF16
@@ -131,20 +132,37 @@ def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=Non
         dtype = SDVG_F32
     else:
         raise TypeError("q must be bfloat16 or float32")
+    cache_len = int(cache_len)
+    if q.dim() != 3 or q.stride(2) != 1:
+        raise ValueError("q must be 3-d with unit dim stride")
+    if (k_cache is None) != (v_cache is None):
+        raise ValueError("k_cache and v_cache come together")
     for t in (k_cache, v_cache, k_blk, v_blk):
         if t is not None and (t.dtype != q.dtype or t.dim() != 3 or t.stride(2) != 1):
             raise ValueError("all tensors share q's dtype, are 3-d and have unit dim stride")
+        if t is not None and (t.shape[1] != q.shape[1] or t.shape[2] != q.shape[2]):
+            raise ValueError("all tensors share q's head count and head_dim")
+        if t is not None and t.device != q.device:
+            raise ValueError("all tensors live on q's device")
+    if v_blk.shape != k_blk.shape:
+        raise ValueError("k_blk and v_blk must have the same shape")
+    if cache_len < 0 or (cache_len > 0 and k_cache is None):
+        raise ValueError("cache_len is negative, or positive without a cache")
+    if k_cache is not None and (v_cache.shape != k_cache.shape or cache_len > k_cache.shape[0]):
+        raise ValueError("cache_len exceeds the cache tensors (or k_cache / v_cache differ in shape)")
     if out is None:
         out = torch.empty(q.shape, dtype=q.dtype, device=q.device)
+    elif (out.shape != q.shape or out.dtype != q.dtype or out.stride(2) != 1 or out.device != q.device):
+        raise ValueError("out must match q in shape, dtype and device and have unit dim stride")
     if k_blk.stride() != v_blk.stride() or (k_cache is not None and k_cache.stride() != v_cache.stride()):
         raise ValueError("k and v must share strides")
     kv_ts, kv_hs = (k_cache.stride(0), k_cache.stride(1)) if k_cache is not None else (128, 128)
     d = sdvg_attn_desc(q.shape[0], k_blk.shape[0], q.shape[1], q.shape[2],
                        q.stride(0), q.stride(1), out.stride(0), out.stride(1),
                        kv_ts, kv_hs, k_blk.stride(0), k_blk.stride(1),
-                       (1.0 / math.sqrt(q.shape[2])) if scale is None else float(scale), dtype)
+                       0.0 if scale is None else float(scale), dtype)
     st = lib().sdvg_block_attn(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_blk),
-                               _ptr(v_blk), int(cache_len), _ptr(out), _stream_ptr(stream))
+                               _ptr(v_blk), cache_len, _ptr(out), _stream_ptr(stream))
     if st != 0:
         raise SdvgError(st, "sdvg_block_attn")
     return out

@@ -25,6 +25,7 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "block_attn_params.h"
@@ -67,7 +68,11 @@ __device__ __forceinline__ void wait_vmcnt0() {
 // One wave-level 16-byte-per-lane global -> LDS copy: lane i's 16 bytes land at
 // lds_addr + 16 * i. Written as inline assembly so that the compiler does not serialise
 // successive copies with vmcnt(0) waits; completion is awaited explicitly (wait_vmcnt0)
-// before the workgroup barrier that publishes the tile.
+// before the workgroup barrier that publishes the tile. The statements write M0 and say so in
+// their clobber lists, so the compiler never assumes a value of its own survives them (clang
+// warns that M0 is a reserved register it will not save; that is the intent).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr) {
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
@@ -89,6 +94,7 @@ __device__ __forceinline__ const char *dma16_step(const char *gptr, uint64_t ste
       : "memory", "m0");
   return gptr;
 }
+#pragma clang diagnostic pop
 
 // Workgroup barrier without the fence of __syncthreads (which would also wait for the
 // prefetches still in flight); the compiler-level memory clobbers keep LDS accesses on
@@ -584,12 +590,19 @@ int launch_bf16(const AttnParams &p_in, hipStream_t s) {
   p.total_work = p.n_qtiles * p.n_heads;
   p.work_per_xcd = (p.total_work + 7) / 8;
   constexpr size_t lds_bytes = 2 * kRing * kTileBytes;
-  static bool attr_set = false;  // raising the dynamic LDS limit is idempotent; races are benign
-  if (!attr_set) {
-    SDVG_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
-    attr_set = true;
-  }
+  // The kernel needs more dynamic LDS than the default limit; the limit is raised once per
+  // device (the attribute belongs to the device that is current when it is set).
+  constexpr int kMaxDevices = 64;
+  static std::once_flag attr_once[kMaxDevices];
+  static hipError_t attr_status[kMaxDevices];
+  int dev = 0;
+  SDVG_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SDVG_ERR_UNSUPPORTED;
+  std::call_once(attr_once[dev], [dev] {
+    attr_status[dev] = hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  });
+  SDVG_HIP_CHECK(attr_status[dev]);
   hipLaunchKernelGGL(block_attn_bf16_kernel, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes, s, p);
   SDVG_HIP_CHECK(hipGetLastError());
   return SDVG_OK;
@@ -606,7 +619,9 @@ extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const 
   if (desc->n_q < 1 || desc->n_blk < 1 || desc->n_heads < 1) return SDVG_ERR_SHAPE;
   if (cache_len < 0 || cache_len + desc->n_blk > INT32_MAX) return SDVG_ERR_RANGE;
   if (cache_len > 0 && (!k_cache || !v_cache)) return SDVG_ERR_NULL;
-  if (!(desc->scale > 0.f) || !isfinite(desc->scale)) return SDVG_ERR_RANGE;
+  // scale == 0 selects the models' default 1/sqrt(head_dim); anything else must be finite and > 0
+  if (!(desc->scale >= 0.f) || !isfinite(desc->scale)) return SDVG_ERR_RANGE;
+  const float scale = desc->scale == 0.f ? 1.0f / sqrtf(static_cast<float>(desc->head_dim)) : desc->scale;
   const int64_t strides[] = {desc->q_token_stride, desc->q_head_stride, desc->o_token_stride,
                              desc->o_head_stride,  desc->blk_token_stride, desc->blk_head_stride};
   for (int64_t st : strides) {
@@ -644,7 +659,7 @@ extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const 
   p.n_q = desc->n_q;
   p.n_k = static_cast<int32_t>(cache_len + desc->n_blk);
   p.n_heads = desc->n_heads;
-  p.scale_log2e = desc->scale * 1.4426950408889634f;
+  p.scale_log2e = scale * 1.4426950408889634f;
   if (desc->dtype == SDVG_F32) return sdvg::launch_block_attn_f32(p, static_cast<hipStream_t>(stream));
   return launch_bf16(p, static_cast<hipStream_t>(stream));
 }

@@ -102,7 +102,28 @@ int validate_cache(const sdvg_kv_cache *c) {
   if (c->head_stride < 128 || c->token_stride < 128 || c->layer_stride < 128) return SDVG_ERR_SHAPE;
   if ((c->head_stride | c->token_stride | c->layer_stride) & 7) return SDVG_ERR_ALIGN;
   if (!sdvg::aligned16(c->k) || !sdvg::aligned16(c->v)) return SDVG_ERR_ALIGN;
+  // Rows must not overlap: of the token and head strides the larger one has to step over
+  // everything the smaller one spans, and (with several layers) a layer over both.
+  const bool token_inner = c->token_stride <= c->head_stride;
+  const int64_t s_in = token_inner ? c->token_stride : c->head_stride;
+  const int64_t n_in = token_inner ? c->capacity_tokens : c->n_heads;
+  const int64_t s_out = token_inner ? c->head_stride : c->token_stride;
+  const int64_t n_out = token_inner ? c->n_heads : c->capacity_tokens;
+  const int64_t span_in = (n_in - 1) * s_in + 128;
+  if (n_out > 1 && s_out < span_in) return SDVG_ERR_SHAPE;
+  if (c->n_layers > 1 && c->layer_stride < (n_out - 1) * s_out + span_in) return SDVG_ERR_SHAPE;
   return SDVG_OK;
+}
+
+// Elements from the first to one past the last element of tokens [first, first + n) of one layer.
+int64_t token_range_span(const sdvg_kv_cache *c, int64_t n) {
+  return (n - 1) * c->token_stride + (c->n_heads - 1) * c->head_stride + 128;
+}
+
+// True if [a, a + a_bytes) and [b, b + b_bytes) share a byte.
+bool ranges_overlap(const void *a, int64_t a_bytes, const void *b, int64_t b_bytes) {
+  const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+  return x < y + static_cast<uintptr_t>(b_bytes) && y < x + static_cast<uintptr_t>(a_bytes);
 }
 
 bool dense_token_major(const sdvg_kv_cache *c) {
@@ -124,6 +145,17 @@ extern "C" int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const voi
   const int64_t T = cache->block_tokens;
   if (slot < 0 || slot * T != cache->cache_len || (slot + 1) * T > cache->capacity_tokens)
     return SDVG_ERR_RANGE;
+  // The source must not alias the slot it is copied into (in any layer): the copy kernels read
+  // and write in no particular order.
+  const int64_t src_bytes = static_cast<int64_t>(cache->n_layers) * T * cache->n_heads * 128 * 2;
+  const int64_t dst_bytes = token_range_span(cache, T) * 2;
+  for (int l = 0; l < cache->n_layers; ++l) {
+    const int64_t off = (l * cache->layer_stride + slot * T * cache->token_stride) * 2;
+    const char *dk = static_cast<const char *>(cache->k) + off, *dv = static_cast<const char *>(cache->v) + off;
+    for (const void *src : {k_blk, v_blk})
+      if (ranges_overlap(src, src_bytes, dk, dst_bytes) || ranges_overlap(src, src_bytes, dv, dst_bytes))
+        return SDVG_ERR_RANGE;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t chunks_per_layer = T * cache->n_heads * 16;
   if (dense_token_major(cache)) {

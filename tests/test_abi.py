@@ -72,7 +72,8 @@ FAKE = 0x1000  # a 16-byte aligned non-null address; never dereferenced (validat
     (dict(kv_head_stride=132), dict(cache_len=8), -4),
     (dict(), dict(q=FAKE + 8), -4),
     (dict(), dict(cache_len=-1), -3),
-    (dict(scale=0.0), dict(), -3),
+    (dict(scale=-1.0), dict(), -3),
+    (dict(scale=float("inf")), dict(), -3),
     (dict(scale=float("nan")), dict(), -3),
 ])
 def test_block_attn_rejects_bad_arguments(P, kw, args, expect):
@@ -105,6 +106,12 @@ def make_cache(P, **kw):
     (dict(), -1, FAKE, -3),
     (dict(cache_len=12), 3, FAKE, -3),   # full
     (dict(cache_len=13), 1, FAKE, -3),   # inconsistent descriptor
+    (dict(layer_stride=11 * 256), 1, FAKE, -2),              # a layer does not hold capacity_tokens
+    (dict(token_stride=128, head_stride=128), 1, FAKE, -2),  # heads of one token overlap
+    (dict(token_stride=128, head_stride=11 * 128, layer_stride=24 * 128), 1, FAKE, -2),  # head-major, head too short
+    (dict(k=0x100000, layer_stride=12 * 256), 1, 0x100000 + 4 * 256 * 2, -3),        # source is the slot itself
+    (dict(k=0x100000, layer_stride=12 * 256), 1, 0x100000 + 7 * 256 * 2 + 16, -3),   # source overlaps the slot's tail
+    (dict(k=0x100000, v=0x200000), 1, 0x200000 + 12 * 256 * 2 + 5 * 256 * 2, -3),    # overlaps layer 1's slot of v
 ])
 def test_kv_commit_rejects_bad_arguments(P, kw, slot, blk, expect):
     c = make_cache(P, **kw)
@@ -151,6 +158,49 @@ def test_buffer_snapshot_rejects_bad_arguments(P):
     assert f(FAKE, FAKE + 4096 + 4, 16, None) == -4
     assert f(FAKE, FAKE + 16, 32, None) == -3          # overlapping ranges
     assert f(FAKE + 16, FAKE, 32, None) == -3
+
+
+def test_kv_descriptor_layouts_accepted(P):
+    # token-major and head-major layouts that keep rows and layers apart pass validation
+    # (rollback to the current length launches nothing)
+    for kw in (dict(), dict(token_stride=128, head_stride=12 * 128, layer_stride=24 * 128),
+               dict(n_layers=1, layer_stride=128)):
+        c = make_cache(P, **kw)
+        assert P.lib().sdvg_kv_rollback(ctypes.byref(c), 4, None) == 0, kw
+
+
+def test_binding_checks_shapes_before_the_call(P, monkeypatch):
+    """binding.block_attn rejects inconsistent tensors with ValueError before the C call (CPU
+    tensors pass for the device check only because the check is patched out here)."""
+    import torch
+    b = P.binding
+    monkeypatch.setattr(b, "_check_dev", lambda *a: None)
+
+    class Trap:
+        def __getattr__(self, name):
+            raise AssertionError("the C library must not be reached")
+    monkeypatch.setattr(b, "_LIB", Trap())
+    bf = torch.bfloat16
+    q = torch.zeros(8, 2, 128, dtype=bf)
+    kb = torch.zeros(8, 2, 128, dtype=bf)
+    kc = torch.zeros(16, 2, 128, dtype=bf)
+    bad = [
+        dict(k_cache=kc, v_cache=kc, cache_len=17),                                  # longer than the cache
+        dict(k_cache=kc, v_cache=kc, cache_len=-1),
+        dict(k_cache=None, v_cache=None, cache_len=4),                               # no cache given
+        dict(k_cache=torch.zeros(16, 3, 128, dtype=bf), v_cache=torch.zeros(16, 3, 128, dtype=bf), cache_len=4),
+        dict(k_cache=kc, v_cache=torch.zeros(12, 2, 128, dtype=bf), cache_len=4),
+        dict(k_cache=kc, v_cache=kc, cache_len=4, k_blk=torch.zeros(8, 4, 128, dtype=bf)),
+        dict(k_cache=kc, v_cache=kc, cache_len=4, v_blk=torch.zeros(6, 2, 128, dtype=bf)),
+        dict(k_cache=kc, v_cache=kc, cache_len=4, out=torch.zeros(7, 2, 128, dtype=bf)),
+        dict(k_cache=kc, v_cache=kc, cache_len=4, out=torch.zeros(8, 2, 128, dtype=torch.float32)),
+        dict(k_cache=kc, v_cache=kc, cache_len=4, out=torch.zeros(8, 2, 256, dtype=bf)[:, :, ::2]),
+    ]
+    for kw in bad:
+        args = dict(q=q, k_cache=kc, v_cache=kc, k_blk=kb, v_blk=kb, cache_len=4)
+        args.update(kw)
+        with pytest.raises(ValueError):
+            b.block_attn(**args)
 
 
 def test_missing_library_fails_loudly(P, monkeypatch):

@@ -218,15 +218,3 @@ def test_library_sdpa_float64(dtype):
     ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0].permute(1, 0, 2).numpy()
     assert ref.dtype == np.float64
     assert np.max(np.abs(out - ref)) < 1e-12
-
-
-def test_planted_mistakes_are_caught():
-    # Sanity of the pins themselves: emulate plausible oracle bugs in numpy and check that the
-    # closed-form tests above would have separated them from the right answer.
-    a, b = 3.0, 2.0
-    right = math.tanh(a * b / math.sqrt(D))
-    wrong_scale = math.tanh(a * b / D)            # 1/d instead of 1/sqrt(d)
-    no_scale = math.tanh(a * b)                   # dropped scale
-    wrong_sign = -right                            # swapped values / negated logits
-    for w in (wrong_scale, no_scale, wrong_sign):
-        assert abs(w - right) > 1e-2

@@ -207,6 +207,22 @@ def test_mean_route_exact_values_and_closed_form_accept_probability():
         assert abs(acc - p) < 4 * math.sqrt(p * (1 - p) / (n // 3)) + 1e-3
 
 
+def test_mean_route_of_opposite_infinities_is_the_canonical_nan():
+    # +inf and -inf among the rewards: the fp64 sum is NaN. Reading taken (the paper is silent):
+    # such a block is unscorable, so it rejects and reports the canonical quiet NaN, exactly as a
+    # NaN reward does. One infinity alone stays an ordinary value.
+    for s in ([np.inf, -np.inf], [0.5, -np.inf, np.inf, 1.0], [np.inf, 2.0, -np.inf]):
+        dec, qb = oracle.route(np.array(s, np.float32), -1e30, 3, mode="mean")
+        assert dec == 0 and qb.view(np.uint32) == 0x7FC00000
+    dec, qb = oracle.route(np.array([np.inf, 1.0], np.float32), 0.0, 3, mode="mean")
+    assert dec == 1 and qb == np.inf
+    dec, qb = oracle.route(np.array([-np.inf, 1.0], np.float32), 0.0, 3, mode="mean")
+    assert dec == 0 and qb == -np.inf
+    # the minimum of the same scores is an ordinary -inf, not a NaN
+    dec, qb = oracle.route(np.array([np.inf, -np.inf], np.float32), 0.0, 3)
+    assert dec == 0 and qb == -np.inf
+
+
 def test_buffer_copy_is_a_byte_copy_and_touches_nothing_else():
     # Sec. 3 "Inference flow": clone before scoring, restore on rejection. Pins: the copy equals
     # numpy's own slice assignment, leaves the bytes around it alone, and clone -> mutate ->
