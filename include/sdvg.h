@@ -78,7 +78,10 @@ typedef struct {
  *   out       device [n_q][n_heads][128], same dtype as the inputs; every element is written.
  *   Arithmetic (bf16): products on the matrix cores with fp32 accumulation, fp32 softmax
  *   statistics, probabilities rounded to bf16 before the PV product (the row sum is taken over
- *   the rounded values), bf16 output (RNE). SDVG_F32 is a slow all-fp32 check path.
+ *   the rounded values), bf16 output (RNE). SDVG_F32 is a slow all-fp32 check path: a separate,
+ *   simple kernel that validates the mathematics (softmax over the concatenation) to 1e-4; it
+ *   shares no tiling or copy logic with the bf16 kernel and says nothing about that kernel's
+ *   indexing.
  *   scale must be finite and >= 0 (0 = 1/sqrt(head_dim)), else SDVG_ERR_RANGE. Inputs are
  *   assumed finite.
  * Asynchronous: enqueued on `stream`; returns SDVG_OK or a negative status. The call only

@@ -28,6 +28,7 @@
 #include <mutex>
 #include <type_traits>
 
+#include "block_attn_index.h"
 #include "block_attn_params.h"
 #include "sdvg_common.h"
 
@@ -43,10 +44,12 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-constexpr int kBN = 64;                 // keys per tile
-constexpr int kBM = 256;                // query rows per workgroup
-constexpr int kRing = 4;                // LDS ring depth (tiles) for K and for V
-constexpr int kTileBytes = kBN * 256;   // one 64-key x 128-dim bf16 tile, unpadded
+namespace ix = sdvg::attn_index;
+using ix::kBN;         // keys per tile
+using ix::kRing;       // LDS ring depth (tiles) for K and for V
+using ix::kTileBytes;  // one 64-key x 128-dim bf16 tile, unpadded
+using ix::kVBase;      // the V ring follows the K ring
+constexpr int kBM = 256;  // query rows per workgroup
 constexpr float kPSumLimit = 1048576.0f;  // 2^20: a tile whose P sums past this retakes the maximum
 
 // v_permlane32_swap(x, x) returns {own, partner} in the lower half-wave and {partner, own} in
@@ -108,11 +111,10 @@ __device__ __forceinline__ void wg_barrier() {
 __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   char *lds_base = reinterpret_cast<char *>(smem);  // K ring at 0, V ring after it
-  constexpr int kVBase = kRing * kTileBytes;
   const uint32_t lds_addr0 =
       static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds_base));
 
-  const int work = (blockIdx.x % 8) * p.work_per_xcd + blockIdx.x / 8;
+  const int work = ix::work_of_block(blockIdx.x, p.work_per_xcd);
   if (work >= p.total_work) return;
   const int head = work / p.n_qtiles;
   const int qt = work - head * p.n_qtiles;
@@ -127,8 +129,8 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   // The head's 32-row wave tiles are dealt out evenly over its workgroups, so that when they do
   // not fill the last workgroup the idle waves are spread one per workgroup: every workgroup of
   // a head then streams K/V at the same pace and the re-reads stay in the XCD's L2.
-  const int wt_count = p.wt_base + (qt < p.wt_rem ? 1 : 0);
-  const int wt_first = qt * p.wt_base + (qt < p.wt_rem ? qt : p.wt_rem);
+  const int wt_count = ix::wave_tiles_of_qtile(qt, p.wt_base, p.wt_rem);
+  const int wt_first = ix::first_wave_tile_of_qtile(qt, p.wt_base, p.wt_rem);
   const int q_row = (wt_first + wave) * 32 + r32;
   const int q_row_ld = q_row < p.n_q ? q_row : p.n_q - 1;
   bf16x8 qf[8];
@@ -138,84 +140,45 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
   }
 
+  // ---- loader (index arithmetic in block_attn_index.h): each wave-level copy writes 1 KB of
+  // LDS = 4 tile rows with the bank-conflict swizzle applied on the global side; every lane
+  // keeps the global address of its two rows of the K stream and of the V stream.
+  ix::Streams st;
+  st.kc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.k_cache) + head * p.kv_hs);
+  st.vc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.v_cache) + head * p.kv_hs);
+  st.kb = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.k_blk) + head * p.blk_hs);
+  st.vb = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.v_blk) + head * p.blk_hs);
+  st.kv_tsb = static_cast<uint32_t>(p.kv_ts * 2);
+  st.blk_tsb = static_cast<uint32_t>(p.blk_ts * 2);
+  st.c_len = static_cast<int>(p.cache_len);
+  st.n_k = p.n_k;
+  const ix::Geometry geo = ix::make_geometry(st);
   const int n_k = p.n_k;
-  const int n_tiles = (n_k + kBN - 1) / kBN;
-
-  // ---- loader: each wave-level copy writes 1 KB of LDS = 4 tile rows; lane i lands at row
-  // i / 16, physical chunk i % 16 of that block and fetches the logical chunk the swizzle maps
-  // there (K: chunk ^ (row & 15); V: chunk ^ 4 * (row & 3)). Every lane keeps the global address
-  // of its two rows of the K stream and of the V stream.
-  const char *kc_base = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.k_cache) + head * p.kv_hs);
-  const char *vc_base = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.v_cache) + head * p.kv_hs);
-  const char *kb_base = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.k_blk) + head * p.blk_hs);
-  const char *vb_base = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.v_blk) + head * p.blk_hs);
-  const uint32_t kv_tsb = static_cast<uint32_t>(p.kv_ts * 2), blk_tsb = static_cast<uint32_t>(p.blk_ts * 2);
-  const int c_len = static_cast<int>(p.cache_len);
-  const int ld_row_in_blk = lane >> 4, ld_p = lane & 15;
-  const int t_seam_lo = c_len / kBN;              // first tile that holds a block token
-  const int t_seam_hi = (c_len + kBN - 1) / kBN;  // first tile wholly inside the block
-  const uint64_t step_c = static_cast<uint64_t>(kBN) * kv_tsb, step_b = static_cast<uint64_t>(kBN) * blk_tsb;
-  const char *k_ptr[2], *v_ptr[2];
-  auto row_ptrs = [&](int t, int u) __attribute__((always_inline)) {
-    const int row = 4 * (wave + 8 * u) + ld_row_in_blk;
-    int j = t * kBN + row;
-    j = j < n_k ? j : n_k - 1;  // rows past the last key re-read it; masked in the softmax
-    const bool in_cache = j < c_len;
-    const uint32_t jj = static_cast<uint32_t>(in_cache ? j : j - c_len);
-    const uint64_t row_off = static_cast<uint64_t>(jj) * (in_cache ? kv_tsb : blk_tsb);
-    k_ptr[u] = (in_cache ? kc_base : kb_base) + row_off + (ld_p ^ (row & 15)) * 16;
-    v_ptr[u] = (in_cache ? vc_base : vb_base) + row_off + (ld_p ^ (4 * (row & 3))) * 16;
-  };
-  // Moves the row pointers to tile t (called with t = 0, 1, 2, ... in order). Tiles that hold
-  // the cache/block seam, the first tile wholly in the block, and the ragged last tile recompute
-  // the pointers; every other tile is one 64-token step from its predecessor.
-  const int t_ragged = n_k / kBN;  // first tile with a row past the last key (== n_tiles if none)
-  auto advance_ptrs = [&](int t) __attribute__((always_inline)) {
-    const bool special = t == 0 || static_cast<unsigned>(t - t_seam_lo) <= static_cast<unsigned>(t_seam_hi - t_seam_lo) ||
-                         t >= t_ragged;
-    if (__builtin_expect(special, 0)) {
-      asm volatile("" ::: "memory");  // a real branch: keep the address arithmetic off the fast path
-      row_ptrs(t, 0);
-      row_ptrs(t, 1);
-    } else {
-      const uint64_t step = t < t_seam_lo ? step_c : step_b;
-      k_ptr[0] += step;
-      k_ptr[1] += step;
-      v_ptr[0] += step;
-      v_ptr[1] += step;
-    }
-  };
+  const int n_tiles = geo.n_tiles;
+  ix::Cursor cur;
   // Starts copy number i (K rows 0-31, K rows 32-63, V rows 0-31, V rows 32-63 of this wave's
   // share) of the tile at the row pointers into ring slot `slot`.
-  auto issue_copy = [&](int slot, int i) __attribute__((always_inline)) {
-    const uint32_t dst = lds_addr0 + slot * kTileBytes + wave * 1024 + (i & 1) * 8 * 1024 +
-                         (i >> 1) * kVBase;
-    dma16(i < 2 ? k_ptr[i] : v_ptr[i - 2], dst);
-  };
   auto issue_tile = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) issue_copy(slot, i);
+    for (int i = 0; i < 4; ++i)
+      dma16(i < 2 ? cur.ptrs.k[i] : cur.ptrs.v[i - 2], lds_addr0 + ix::copy_dst(slot, wave, i));
   };
   // Plain tiles: step the pointer by 64 tokens and start the copy in one go.
   auto step_copy = [&](int slot, int i, uint64_t step) __attribute__((always_inline)) {
-    const uint32_t dst = lds_addr0 + slot * kTileBytes + wave * 1024 + (i & 1) * 8 * 1024 +
-                         (i >> 1) * kVBase;
+    const uint32_t dst = lds_addr0 + ix::copy_dst(slot, wave, i);
     if (i < 2)
-      k_ptr[i] = dma16_step(k_ptr[i], step, dst);
+      cur.ptrs.k[i] = dma16_step(cur.ptrs.k[i], step, dst);
     else
-      v_ptr[i - 2] = dma16_step(v_ptr[i - 2], step, dst);
+      cur.ptrs.v[i - 2] = dma16_step(cur.ptrs.v[i - 2], step, dst);
   };
 
   // ---- LDS read addresses (bytes)
   int k_off[8];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) k_off[s] = r32 * 256 + (((2 * s + hh) ^ (r32 & 15)) * 16);
-  const int i16 = lane & 15, b16 = (lane >> 4) & 1;
+  for (int s = 0; s < 8; ++s) k_off[s] = ix::k_read_offset(lane, s, 0);
   int v_off[4];
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
-    v_off[db] = kVBase + (4 * hh + (i16 >> 2)) * 256 + ((db ^ (i16 >> 2)) * 64) + 32 * b16 +
-                8 * (i16 & 3);
+  for (int db = 0; db < 4; ++db) v_off[db] = kVBase + ix::v_read_offset(lane, 0, db, 0);
 
   f32x16 o_acc[4];
 #pragma unroll
@@ -435,33 +398,15 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
         if (key0 + kb * 32 + 8 * (i >> 2) + (i & 3) >= n_k) s_acc[kb][i] = -INFINITY;
   };
 
-  // ---- rare events of the tile loop. Tile t starts the copies of tile t+3 by stepping the row
-  // pointers 64 tokens on. That is wrong when tile t+3 holds the cache/block seam, is the
-  // first tile wholly inside the block, is the ragged last tile, or does not exist; for those
-  // t (t == t_evt) the pointers are set beforehand so that the step lands on the right rows
-  // (past the end: on the last tile again, a harmless redundant copy).
-  uint64_t fast_step = 3 < t_seam_lo ? step_c : step_b;
-  const int g_lo = t_seam_lo - 3, g_hi = t_seam_hi - 3;
-  const int g_end = (t_ragged < n_tiles ? t_ragged : n_tiles) - 3;
-  auto next_event = [&](int x) __attribute__((always_inline)) -> int {
-    if (x >= g_lo && x <= g_hi) return x;
-    const int e = x > g_end ? x : g_end;
-    return (x < g_lo && g_lo < e) ? g_lo : e;
-  };
-  int t_evt = next_event(0);
-  bool mask_next = false;  // the scores produced by this tile's matrix phase need the tail mask
+  // ---- rare events of the tile loop (block_attn_index.h, on_event): tile t starts the copies
+  // of tile t+3 by stepping the row pointers 64 tokens on; where that is wrong (seam, first tile
+  // wholly in the block, ragged last tile, past the end) the pointers are re-based beforehand.
+  cur.fast_step = ix::first_fast_step(geo);
+  cur.t_evt = ix::next_event(geo, 0);
+  cur.mask_next = false;
   auto on_event = [&](int t) __attribute__((always_inline)) {
     asm volatile("" ::: "memory");  // a real branch: keep this arithmetic off the fast path
-    const int tau = t + 3 < n_tiles ? t + 3 : n_tiles - 1;
-    fast_step = t + 3 >= n_tiles ? 0 : (tau + 1 < t_seam_lo ? step_c : step_b);
-    row_ptrs(tau, 0);
-    row_ptrs(tau, 1);
-    k_ptr[0] -= fast_step;
-    k_ptr[1] -= fast_step;
-    v_ptr[0] -= fast_step;
-    v_ptr[1] -= fast_step;
-    mask_next = t + 1 == n_tiles - 1 && t_ragged < n_tiles;
-    t_evt = next_event(t + 1);
+    ix::on_event(st, geo, t, wave, lane, cur);
   };
 
   // One tile: vector phase (softmax of S(t)), barrier, matrix phase (copies of tile t+3 started
@@ -485,13 +430,13 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     wait_vmcnt0();  // this wave's copies issued in the previous matrix phase have landed
     wg_barrier();
     __builtin_amdgcn_s_setprio(1);
-    if (__builtin_expect(t == t_evt, 0)) on_event(t);
+    if (__builtin_expect(t == cur.t_evt, 0)) on_event(t);
     // Each of the four QK groups also starts one of the four copies of tile t+3.
-    qk_group(fa, fb, Rn, 0, R, Rp, fast_step);
-    qk_group(fb, fa, Rn, 1, R, Rp, fast_step);
-    qk_group(fa, fb, Rn, 2, R, Rp, fast_step);
-    qk_group(fb, fa, Rn, 3, R, Rp, fast_step);  // leaves V group 0 in fa
-    if (__builtin_expect(mask_next, 0)) mask_tail(t + 1);
+    qk_group(fa, fb, Rn, 0, R, Rp, cur.fast_step);
+    qk_group(fb, fa, Rn, 1, R, Rp, cur.fast_step);
+    qk_group(fa, fb, Rn, 2, R, Rp, cur.fast_step);
+    qk_group(fb, fa, Rn, 3, R, Rp, cur.fast_step);  // leaves V group 0 in fa
+    if (__builtin_expect(cur.mask_next, 0)) mask_tail(t + 1);
     pv_group(fa, fb, R, 0);
     pv_group(fb, fa, R, 1);
     pv_group(fa, fb, R, 2);
@@ -505,7 +450,12 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
 #pragma unroll
   for (int t = 0; t < 3; ++t) {
     if (t < n_tiles) {
-      advance_ptrs(t);
+      if (ix::tile_is_special(geo, t)) {
+        ix::row_ptrs(st, t, 0, wave, lane, cur.ptrs);
+        ix::row_ptrs(st, t, 1, wave, lane, cur.ptrs);
+      } else {
+        ix::step_ptrs(cur.ptrs, t < geo.t_seam_lo ? geo.step_c : geo.step_b);
+      }
       issue_tile(t);
     }
   }
@@ -519,10 +469,10 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     for (int t = 0; t < n_tiles; ++t) {
       wait_vmcnt0();
       wg_barrier();
-      if (t == t_evt) on_event(t);
+      if (t == cur.t_evt) on_event(t);
       const int rp = (t + 3) & (kRing - 1);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) step_copy(rp, i, fast_step);
+      for (int i = 0; i < 4; ++i) step_copy(rp, i, cur.fast_step);
       wg_barrier();
     }
     wait_vmcnt0();

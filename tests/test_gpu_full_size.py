@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import sdvg_inputs as si
-from gpu_util import BF16_MAX_ABS, BF16_REL_RMS, attn_errors
+from gpu_util import BF16_MAX_ABS, BF16_REL_RMS, attn_errors_by_head
 
 pytestmark = pytest.mark.gpu
 
@@ -39,8 +39,11 @@ def attn_case(H, cache_len, seed, jitter=False, heads=None, rows=None):
     ref = oracle.block_attn(f(q[:, hsel]), f(kc[:max(cache_len, 1), hsel]), f(vc[:max(cache_len, 1), hsel]),
                             f(kb[:, hsel]), f(vb[:, hsel]), cache_len, rows=rows)
     got = f(out[:, hsel])[rows]
-    max_abs, rel = attn_errors(got, ref)
-    assert max_abs <= BF16_MAX_ABS and rel <= BF16_REL_RMS, (max_abs, rel)
+    max_abs, rel, worst_rel, worst_head = attn_errors_by_head(got, ref)
+    print("H=%d cache_len=%d: max|err| %.3e, rel-RMS pooled %.3e, worst head %d: %.3e"
+          % (H, cache_len, max_abs, rel, worst_head, worst_rel))
+    # the bounds hold for every single head, not only for the pooled figure
+    assert max_abs <= BF16_MAX_ABS and rel <= BF16_REL_RMS and worst_rel <= BF16_REL_RMS, (max_abs, rel, worst_rel)
     return max_abs, rel
 
 
