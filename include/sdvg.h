@@ -35,6 +35,9 @@ typedef enum {
 
 enum { SDVG_BF16 = 0, SDVG_F32 = 1 };
 
+/* Key-split policy of sdvg_block_attn_batch (see there). */
+enum { SDVG_SPLIT_NEVER = 0, SDVG_SPLIT_AUTO = 1, SDVG_SPLIT_ALWAYS = 2 };
+
 /*
  * Describes the caller-owned KV cache of one model: two device arrays k and v of bf16,
  * logical [n_layers][capacity_tokens][n_heads][head_dim]. cache_len is a HOST field: the
@@ -92,6 +95,48 @@ typedef struct {
 int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cache,
                     const void *v_cache, const void *k_blk, const void *v_blk,
                     int64_t cache_len, void *out, void *stream);
+
+/*
+ * The same attention for up to 8 independent (q, cache, block, out) sets in ONE launch -- e.g. the
+ * conditional and the unconditional pass of classifier-free guidance (paper Sec. 4.1 "Models":
+ * guidance scale 3.0), which share shapes and cache length but have their own tensors. Result
+ * item by item as n_items calls of sdvg_block_attn; one launch fills the chip better and halves
+ * the launch count.
+ *   n_items   1 .. 8. q, k_cache, v_cache, k_blk, v_blk, out: HOST arrays of n_items device
+ *             pointers (k_cache / v_cache and their entries may be NULL when cache_len == 0).
+ *             All items share desc (shapes, strides, scale, dtype) and cache_len.
+ *   workspace device, nullable, 16-byte aligned, workspace_bytes long; split_mode one of
+ *             SDVG_SPLIT_*. Without a workspace (or with SDVG_SPLIT_NEVER) every query tile of
+ *             256 rows is one workgroup. With a workspace of at least
+ *             sdvg_block_attn_workspace_bytes(desc, n_items, cache_len, split_mode) bytes the
+ *             library may deal the (query tile, key tile) pairs out evenly over whole rounds of
+ *             workgroups instead, so that a launch with few query tiles still fills the chip,
+ *             and merge the partial results of the query tiles that were cut in a second small
+ *             kernel on the same stream. SDVG_SPLIT_AUTO does so when at least 60 % of the last
+ *             round of workgroups would idle (very few heads or short blocks); SDVG_SPLIT_ALWAYS
+ *             whenever the query tiles do not fill whole rounds. For the paper's own shapes the
+ *             split does not pay (a 12-head drafter layer has 228 query tiles for 256 compute
+ *             units; the split costs more than the 11 % it could win) and AUTO leaves them alone.
+ *             Same softmax and same error bounds; not bit-identical to the unsplit result (P is
+ *             rounded to bf16 against each piece's own running maximum). A workspace that is
+ *             too small is ignored (plain launch). The workspace is scratch: contents are
+ *             undefined afterwards; concurrent calls need their own.
+ * Errors as sdvg_block_attn, plus SDVG_ERR_SHAPE for n_items outside 1 .. 8 or a negative
+ * workspace_bytes and SDVG_ERR_UNSUPPORTED for an unknown split_mode. Asynchronous on `stream`.
+ */
+int sdvg_block_attn_batch(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q,
+                          const void *const *k_cache, const void *const *v_cache,
+                          const void *const *k_blk, const void *const *v_blk, int64_t cache_len,
+                          void *const *out, void *workspace, int64_t workspace_bytes,
+                          int32_t split_mode, void *stream);
+
+/*
+ * Bytes of workspace with which sdvg_block_attn_batch would split keys for this shape and
+ * split_mode on the current device; 0 if it would not split (then no workspace is needed).
+ * Negative sdvg_status on a bad descriptor.
+ */
+int64_t sdvg_block_attn_workspace_bytes(const sdvg_attn_desc *desc, int32_t n_items, int64_t cache_len,
+                                        int32_t split_mode);
 
 /*
  * KV commit (paper Sec. 3 "Inference flow": an accepted draft block is committed to the

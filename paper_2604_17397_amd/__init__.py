@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     SdvgError,
     KVCache,
     block_attn,
+    block_attn_batch,
+    block_attn_workspace_bytes,
     kv_commit,
     kv_rollback,
     buffer_snapshot,

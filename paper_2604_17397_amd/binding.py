@@ -12,6 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsdvg.so")
 
 SDVG_BF16, SDVG_F32 = 0, 1
+SDVG_SPLIT_NEVER, SDVG_SPLIT_AUTO, SDVG_SPLIT_ALWAYS = 0, 1, 2
+_SPLIT = {"never": 0, "auto": 1, "always": 2}
 
 
 class SdvgError(RuntimeError):
@@ -54,6 +56,12 @@ def lib():
         vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
         L.sdvg_block_attn.restype = ctypes.c_int
         L.sdvg_block_attn.argtypes = [ctypes.POINTER(sdvg_attn_desc), vp, vp, vp, vp, vp, i64, vp, vp]
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        L.sdvg_block_attn_batch.restype = ctypes.c_int
+        L.sdvg_block_attn_batch.argtypes = [ctypes.POINTER(sdvg_attn_desc), i32, pp, pp, pp, pp, pp, i64, pp,
+                                            vp, i64, i32, vp]
+        L.sdvg_block_attn_workspace_bytes.restype = ctypes.c_int64
+        L.sdvg_block_attn_workspace_bytes.argtypes = [ctypes.POINTER(sdvg_attn_desc), i32, i64, i32]
         L.sdvg_kv_commit.restype = ctypes.c_int
         L.sdvg_kv_commit.argtypes = [ctypes.POINTER(sdvg_kv_cache), vp, vp, i32, vp]
         L.sdvg_kv_rollback.restype = ctypes.c_int
@@ -120,11 +128,10 @@ class KVCache:
         return self.k[i], self.v[i]
 
 
-def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=None, stream=None):
-    """sdvg_block_attn: q, k_blk, v_blk [tokens, heads, 128]; k_cache, v_cache one layer's
-    [>= cache_len, heads, 128] (may be None when cache_len == 0). `scale=None` passes 0, which the
-    library reads as 1/sqrt(head_dim). Returns out. Shapes are checked against each other here,
-    because a wrong length or head count would make the kernel read outside the tensors."""
+def _attn_desc(q, k_cache, v_cache, k_blk, v_blk, cache_len, out, scale):
+    """Checks one (q, cache, block, out) set and returns its descriptor. Shapes are checked
+    against each other here, because a wrong length or head count would make the kernel read
+    outside the tensors."""
     _check_dev(q, k_cache, v_cache, k_blk, v_blk, out)
     if q.dtype == torch.bfloat16:
         dtype = SDVG_BF16
@@ -132,7 +139,6 @@ def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=Non
         dtype = SDVG_F32
     else:
         raise TypeError("q must be bfloat16 or float32")
-    cache_len = int(cache_len)
     if q.dim() != 3 or q.stride(2) != 1:
         raise ValueError("q must be 3-d with unit dim stride")
     if (k_cache is None) != (v_cache is None):
@@ -150,22 +156,82 @@ def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=Non
         raise ValueError("cache_len is negative, or positive without a cache")
     if k_cache is not None and (v_cache.shape != k_cache.shape or cache_len > k_cache.shape[0]):
         raise ValueError("cache_len exceeds the cache tensors (or k_cache / v_cache differ in shape)")
-    if out is None:
-        out = torch.empty(q.shape, dtype=q.dtype, device=q.device)
-    elif (out.shape != q.shape or out.dtype != q.dtype or out.stride(2) != 1 or out.device != q.device):
+    if (out.shape != q.shape or out.dtype != q.dtype or out.stride(2) != 1 or out.device != q.device):
         raise ValueError("out must match q in shape, dtype and device and have unit dim stride")
     if k_blk.stride() != v_blk.stride() or (k_cache is not None and k_cache.stride() != v_cache.stride()):
         raise ValueError("k and v must share strides")
     kv_ts, kv_hs = (k_cache.stride(0), k_cache.stride(1)) if k_cache is not None else (128, 128)
-    d = sdvg_attn_desc(q.shape[0], k_blk.shape[0], q.shape[1], q.shape[2],
-                       q.stride(0), q.stride(1), out.stride(0), out.stride(1),
-                       kv_ts, kv_hs, k_blk.stride(0), k_blk.stride(1),
-                       0.0 if scale is None else float(scale), dtype)
+    return sdvg_attn_desc(q.shape[0], k_blk.shape[0], q.shape[1], q.shape[2],
+                          q.stride(0), q.stride(1), out.stride(0), out.stride(1),
+                          kv_ts, kv_hs, k_blk.stride(0), k_blk.stride(1),
+                          0.0 if scale is None else float(scale), dtype)
+
+
+def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=None, stream=None):
+    """sdvg_block_attn: q, k_blk, v_blk [tokens, heads, 128]; k_cache, v_cache one layer's
+    [>= cache_len, heads, 128] (may be None when cache_len == 0). `scale=None` passes 0, which the
+    library reads as 1/sqrt(head_dim). Returns out."""
+    cache_len = int(cache_len)
+    if out is None:
+        out = torch.empty(q.shape, dtype=q.dtype, device=q.device)
+    d = _attn_desc(q, k_cache, v_cache, k_blk, v_blk, cache_len, out, scale)
     st = lib().sdvg_block_attn(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_blk),
                                _ptr(v_blk), cache_len, _ptr(out), _stream_ptr(stream))
     if st != 0:
         raise SdvgError(st, "sdvg_block_attn")
     return out
+
+
+def _desc_key(d):
+    return tuple(getattr(d, f) for f, _ in d._fields_)
+
+
+def block_attn_workspace_bytes(q, k_cache, v_cache, k_blk, v_blk, cache_len, n_items=1, split="auto", scale=None):
+    """sdvg_block_attn_workspace_bytes for the shape of these tensors; split is "never", "auto" or
+    "always"."""
+    cache_len = int(cache_len)
+    d = _attn_desc(q, k_cache, v_cache, k_blk, v_blk, cache_len, q, scale)
+    n = lib().sdvg_block_attn_workspace_bytes(ctypes.byref(d), int(n_items), cache_len, _SPLIT[split])
+    if n < 0:
+        raise SdvgError(n, "sdvg_block_attn_workspace_bytes")
+    return int(n)
+
+
+def block_attn_batch(qs, k_caches, v_caches, k_blks, v_blks, cache_len, outs=None, workspace=None,
+                     split="auto", scale=None, stream=None):
+    """sdvg_block_attn_batch: lists of n tensors each (k_caches / v_caches may be None when
+    cache_len == 0); every item must have the same shapes and strides. `workspace`: optional
+    device tensor (any dtype) the library may use to split keys over workgroups, under the policy
+    `split` ("never", "auto", "always"). Returns outs."""
+    cache_len = int(cache_len)
+    n = len(qs)
+    if k_caches is None:
+        k_caches, v_caches = [None] * n, [None] * n
+    if not (len(k_caches) == len(v_caches) == len(k_blks) == len(v_blks) == n):
+        raise ValueError("every list needs one tensor per item")
+    if outs is None:
+        outs = [torch.empty(q.shape, dtype=q.dtype, device=q.device) for q in qs]
+    descs = [_attn_desc(qs[i], k_caches[i], v_caches[i], k_blks[i], v_blks[i], cache_len, outs[i], scale)
+             for i in range(n)]
+    if any(_desc_key(d) != _desc_key(descs[0]) for d in descs[1:]):
+        raise ValueError("all items of a batch must share shapes, strides and dtype")
+    if any(t.device != qs[0].device for t in qs):
+        raise ValueError("all items live on one device")
+
+    def arr(ts):
+        return (ctypes.c_void_p * n)(*[t.data_ptr() if t is not None else None for t in ts])
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        _check_dev(workspace)
+        if not workspace.is_contiguous() or workspace.device != qs[0].device:
+            raise ValueError("workspace must be a contiguous tensor on the items' device")
+        ws_ptr, ws_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
+    st = lib().sdvg_block_attn_batch(ctypes.byref(descs[0]), n, arr(qs), arr(k_caches), arr(v_caches),
+                                     arr(k_blks), arr(v_blks), cache_len, arr(outs), ws_ptr, ws_bytes,
+                                     _SPLIT[split], _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_block_attn_batch")
+    return outs
 
 
 def kv_commit(cache, k_blk, v_blk, slot, stream=None):

@@ -23,6 +23,7 @@
 //   Softmax is in the log2 domain with a lazy running maximum whose negative is carried in the
 //   initial value of the score accumulators (see softmax_tile below).
 #include <math.h>
+#include <stddef.h>
 #include <stdlib.h>
 
 #include <mutex>
@@ -108,16 +109,39 @@ __device__ __forceinline__ void wg_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// The `items` array of the kernels' single by-value AttnParams argument, read from the
+// kernel-argument segment (constant memory; the compiler turns the reads into scalar loads).
+__device__ __forceinline__ const sdvg::AttnItem *kernarg_items() {
+  const char *ka = (const char *)__builtin_amdgcn_kernarg_segment_ptr();
+  return reinterpret_cast<const sdvg::AttnItem *>(ka + offsetof(AttnParams, items));
+}
+
+// Rows of O^T held in the accumulator layout (lane = query row lane % 32, half-wave hh), scaled by
+// 1 / row sum, rounded to bf16 and stored; rows past n_q are not stored.
+__device__ __forceinline__ void store_rows(const AttnParams &p, const sdvg::AttnItem &it, int head, int q_row,
+                                           int hh, const f32x16 (&o_acc)[4], float inv_l) {
+  if (q_row >= p.n_q) return;
+  uint16_t *op = static_cast<uint16_t *>(it.out) + q_row * p.o_ts + head * p.o_hs + 4 * hh;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 o4 = {o_acc[u][4 * g] * inv_l, o_acc[u][4 * g + 1] * inv_l, o_acc[u][4 * g + 2] * inv_l,
+                        o_acc[u][4 * g + 3] * inv_l};
+      const bf16x4 ob = __builtin_convertvector(o4, bf16x4);
+      *reinterpret_cast<bf16x4 *>(op + 32 * u + 8 * g) = ob;
+    }
+  }
+}
+
+// kSplit = false: one piece per workgroup (one query tile with all its key tiles; the hot case).
+// kSplit = true: the workgroup's run may hold several pieces, taken in a loop.
+template <bool kSplit>
 __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   char *lds_base = reinterpret_cast<char *>(smem);  // K ring at 0, V ring after it
   const uint32_t lds_addr0 =
       static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds_base));
-
-  const int work = ix::work_of_block(blockIdx.x, p.work_per_xcd);
-  if (work >= p.total_work) return;
-  const int head = work / p.n_qtiles;
-  const int qt = work - head * p.n_qtiles;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -125,6 +149,33 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   const bool group_b = wave >= 4;
   const int r32 = lane & 31;
   const int hh = lane >> 5;
+
+  // ---- LDS read addresses (bytes)
+  int k_off[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) k_off[s] = ix::k_read_offset(lane, s, 0);
+  int v_off[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) v_off[db] = kVBase + ix::v_read_offset(lane, 0, db, 0);
+
+  // ---- this workgroup's run of (query tile, key tile) pairs (block_attn_index.h, "key split").
+  // Normally the run is exactly one query tile with all its key tiles; when the keys are split it
+  // may end one query tile and begin the next, and the loop below takes the pieces in turn.
+  const int work = ix::work_of_block(blockIdx.x, p.work_per_xcd);
+  if (work >= p.total_work) return;
+  int64_t u_next = static_cast<int64_t>(work) * p.units;
+  const int64_t u_all = static_cast<int64_t>(p.n_hq) * p.n_tiles;
+  const int64_t u_end = u_next + p.units < u_all ? u_next + p.units : u_all;
+  // One piece: a query tile and a run [t_first, t_end) of its key tiles.
+  auto run_piece = [&](const ix::Piece pc) __attribute__((always_inline)) {
+  const int t0 = pc.t_first, t1 = pc.t_end;
+  const int per_item = p.n_heads * p.n_qtiles;
+  const int item = pc.hq / per_item;
+  const int head = (pc.hq - item * per_item) / p.n_qtiles;
+  const int qt = pc.hq - item * per_item - head * p.n_qtiles;
+  // The item's pointers are read from the kernel-argument segment with a run-time index (indexing
+  // the by-value parameter would first pull all items into registers).
+  const sdvg::AttnItem it = kernarg_items()[item];
 
   // The head's 32-row wave tiles are dealt out evenly over its workgroups, so that when they do
   // not fill the last workgroup the idle waves are spread one per workgroup: every workgroup of
@@ -135,7 +186,7 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   const int q_row_ld = q_row < p.n_q ? q_row : p.n_q - 1;
   bf16x8 qf[8];
   {
-    const uint16_t *qp = static_cast<const uint16_t *>(p.q) + q_row_ld * p.q_ts + head * p.q_hs + 8 * hh;
+    const uint16_t *qp = static_cast<const uint16_t *>(it.q) + q_row_ld * p.q_ts + head * p.q_hs + 8 * hh;
 #pragma unroll
     for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + 16 * s);
   }
@@ -144,17 +195,16 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   // LDS = 4 tile rows with the bank-conflict swizzle applied on the global side; every lane
   // keeps the global address of its two rows of the K stream and of the V stream.
   ix::Streams st;
-  st.kc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.k_cache) + head * p.kv_hs);
-  st.vc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.v_cache) + head * p.kv_hs);
-  st.kb = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.k_blk) + head * p.blk_hs);
-  st.vb = reinterpret_cast<const char *>(static_cast<const uint16_t *>(p.v_blk) + head * p.blk_hs);
+  st.kc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(it.k_cache) + head * p.kv_hs);
+  st.vc = reinterpret_cast<const char *>(static_cast<const uint16_t *>(it.v_cache) + head * p.kv_hs);
+  st.kb = reinterpret_cast<const char *>(static_cast<const uint16_t *>(it.k_blk) + head * p.blk_hs);
+  st.vb = reinterpret_cast<const char *>(static_cast<const uint16_t *>(it.v_blk) + head * p.blk_hs);
   st.kv_tsb = static_cast<uint32_t>(p.kv_ts * 2);
   st.blk_tsb = static_cast<uint32_t>(p.blk_ts * 2);
   st.c_len = static_cast<int>(p.cache_len);
   st.n_k = p.n_k;
-  const ix::Geometry geo = ix::make_geometry(st);
+  const ix::Geometry geo = ix::make_geometry(st, t0, t1);
   const int n_k = p.n_k;
-  const int n_tiles = geo.n_tiles;
   ix::Cursor cur;
   // Starts copy number i (K rows 0-31, K rows 32-63, V rows 0-31, V rows 32-63 of this wave's
   // share) of the tile at the row pointers into ring slot `slot`.
@@ -171,14 +221,6 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     else
       cur.ptrs.v[i - 2] = dma16_step(cur.ptrs.v[i - 2], step, dst);
   };
-
-  // ---- LDS read addresses (bytes)
-  int k_off[8];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) k_off[s] = ix::k_read_offset(lane, s, 0);
-  int v_off[4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db) v_off[db] = kVBase + ix::v_read_offset(lane, 0, db, 0);
 
   f32x16 o_acc[4];
 #pragma unroll
@@ -402,7 +444,7 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   // of tile t+3 by stepping the row pointers 64 tokens on; where that is wrong (seam, first tile
   // wholly in the block, ragged last tile, past the end) the pointers are re-based beforehand.
   cur.fast_step = ix::first_fast_step(geo);
-  cur.t_evt = ix::next_event(geo, 0);
+  cur.t_evt = ix::next_event(geo, t0);
   cur.mask_next = false;
   auto on_event = [&](int t) __attribute__((always_inline)) {
     asm volatile("" ::: "memory");  // a real branch: keep this arithmetic off the fast path
@@ -410,8 +452,9 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   };
 
   // One tile: vector phase (softmax of S(t)), barrier, matrix phase (copies of tile t+3 started
-  // between the MFMA groups, S(t+1) = K(t+1) Q^T, then O += P(t) V(t)), barrier. R = t % 4, the ring slot of tile t, is a compile-time constant: the loop is
-  // unrolled by 4 and every LDS address is a base register plus an immediate.
+  // between the MFMA groups, S(t+1) = K(t+1) Q^T, then O += P(t) V(t)), barrier. R = (t - t0) % 4,
+  // the ring slot of tile t, is a compile-time constant: the loop is unrolled by 4 and every LDS
+  // address is a base register plus an immediate.
   // The last tile computes a meaningless S(t+1) from a stale slot; nothing reads it.
   auto tile_body = [&](auto slot, int t) __attribute__((always_inline)) {
     constexpr int R = decltype(slot)::value;
@@ -446,129 +489,237 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     __builtin_amdgcn_s_setprio(0);
     wg_barrier();
   };
-  // ---- prologue: tiles 0..2 into the rings, then S(0)
+  // ---- prologue: the piece's first three tiles into ring slots 0..2, then S of the first
 #pragma unroll
-  for (int t = 0; t < 3; ++t) {
-    if (t < n_tiles) {
+  for (int r = 0; r < 3; ++r) {
+    const int t = t0 + r;
+    if (t < t1) {
       if (ix::tile_is_special(geo, t)) {
         ix::row_ptrs(st, t, 0, wave, lane, cur.ptrs);
         ix::row_ptrs(st, t, 1, wave, lane, cur.ptrs);
       } else {
         ix::step_ptrs(cur.ptrs, t < geo.t_seam_lo ? geo.step_c : geo.step_b);
       }
-      issue_tile(t);
+      issue_tile(r);
     }
   }
   wait_vmcnt0();
   wg_barrier();
 
-  // A wave without a wave tile computes nothing: it only keeps its share of the tile copies
-  // going and takes part in the barriers, so that its SIMD is left to the partner wave.
   if (wave >= wt_count) {
+    // A wave without a wave tile computes nothing: it only keeps its share of the tile copies
+    // going and takes part in the barriers, so that its SIMD is left to the partner wave.
     if (group_b) wg_barrier();
-    for (int t = 0; t < n_tiles; ++t) {
+    for (int t = t0; t < t1; ++t) {
       wait_vmcnt0();
       wg_barrier();
       if (t == cur.t_evt) on_event(t);
-      const int rp = (t + 3) & (kRing - 1);
+      const int rp = (t - t0 + 3) & (kRing - 1);
 #pragma unroll
       for (int i = 0; i < 4; ++i) step_copy(rp, i, cur.fast_step);
       wg_barrier();
     }
     wait_vmcnt0();
     if (!group_b) wg_barrier();
-    return;
-  }
-
-  read_k(fa[0], 0, 0, 0);
-  read_k(fa[1], 0, 0, 1);
-  read_k(fa[2], 0, 1, 0);
-  read_k(fa[3], 0, 1, 1);
-  qk_group(fa, fb, 0, 0, 0);
-  qk_group(fb, fa, 0, 1, 0);
-  qk_group(fa, fb, 0, 2, 0);
-  qk_group(fb, fa, 0, 3, 0);  // (its V read is harmless: slot 0 holds V(0))
-  wait_lds0();
-  if (n_tiles == 1) mask_tail(0);
-  {  // the running maximum starts at tile 0's true maximum
-    const float mx = tile_max();
+  } else {
+    read_k(fa[0], 0, 0, 0);
+    read_k(fa[1], 0, 0, 1);
+    read_k(fa[2], 0, 1, 0);
+    read_k(fa[3], 0, 1, 1);
+    qk_group(fa, fb, 0, 0, 0);
+    qk_group(fb, fa, 0, 1, 0);
+    qk_group(fa, fb, 0, 2, 0);
+    qk_group(fb, fa, 0, 3, 0);  // (its V read is harmless: slot 0 holds V of the first tile)
+    wait_lds0();
+    if (t0 == geo.n_tiles - 1) mask_tail(t0);
+    {  // the running maximum starts at the first tile's true maximum
+      const float mx = tile_max();
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s_acc[kb][i] -= mx;
-    set_shift(-mx);
-  }
-  if (group_b) wg_barrier();  // group B runs one phase behind group A
-
-  for (int t = 0;;) {
-    tile_body(std::integral_constant<int, 0>{}, t);
-    if (++t == n_tiles) break;
-    tile_body(std::integral_constant<int, 1>{}, t);
-    if (++t == n_tiles) break;
-    tile_body(std::integral_constant<int, 2>{}, t);
-    if (++t == n_tiles) break;
-    tile_body(std::integral_constant<int, 3>{}, t);
-    if (++t == n_tiles) break;
-  }
-  wait_vmcnt0();               // the redundant copies of the last tiles must not outlive the wave
-  if (!group_b) wg_barrier();  // pairs with group B's extra barrier at the start
-
-  // ---- epilogue
-  const float l_tot = lane_sum32(l_run);
-  const float inv_l = 1.0f / l_tot;
-  if (q_row < p.n_q) {
-    uint16_t *op = static_cast<uint16_t *>(p.out) + q_row * p.o_ts + head * p.o_hs + 4 * hh;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 o4 = {o_acc[u][4 * g] * inv_l, o_acc[u][4 * g + 1] * inv_l,
-                          o_acc[u][4 * g + 2] * inv_l, o_acc[u][4 * g + 3] * inv_l};
-        const bf16x4 ob = __builtin_convertvector(o4, bf16x4);
-        *reinterpret_cast<bf16x4 *>(op + 32 * u + 8 * g) = ob;
-      }
+        for (int i = 0; i < 16; ++i) s_acc[kb][i] -= mx;
+      set_shift(-mx);
     }
+    if (group_b) wg_barrier();  // group B runs one phase behind group A
+
+    for (int t = t0;;) {
+      tile_body(std::integral_constant<int, 0>{}, t);
+      if (++t == t1) break;
+      tile_body(std::integral_constant<int, 1>{}, t);
+      if (++t == t1) break;
+      tile_body(std::integral_constant<int, 2>{}, t);
+      if (++t == t1) break;
+      tile_body(std::integral_constant<int, 3>{}, t);
+      if (++t == t1) break;
+    }
+    wait_vmcnt0();               // the redundant copies of the last tiles must not outlive the piece
+    if (!group_b) wg_barrier();  // pairs with group B's extra barrier at the start
+
+    // ---- epilogue: the finished rows, or this piece's partial sums for the merge kernel
+    if (pc.whole) {
+      const float inv_l = 1.0f / lane_sum32(l_run);
+      store_rows(p, it, head, q_row, hh, o_acc, inv_l);
+    } else {
+      float *part = p.partials + static_cast<int64_t>(ix::partial_slot(pc.hq, work)) * sdvg::kPartialFloats +
+                    wave * (66 * 64) + lane;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part[(16 * u + i) * 64] = o_acc[u][i];
+      part[64 * 64] = l_run;
+      part[65 * 64] = s_shift;
+    }
+  }
+  };
+  // A run is never longer than one query tile's key tiles, so it holds one piece or two (the end
+  // of one query tile and the start of the next). Two calls rather than a loop: with the piece
+  // body inside a loop the compiler kept so much alive around the back edge that it spilled.
+  const ix::Piece first = ix::piece_at(u_next, u_end, p.n_tiles);
+  run_piece(first);
+  if (kSplit) {
+    u_next += first.t_end - first.t_first;
+    if (u_next < u_end) run_piece(ix::piece_at(u_next, u_end, p.n_tiles));
   }
 }
 
-int launch_bf16(const AttnParams &p_in, hipStream_t s) {
-  AttnParams p = p_in;
-  p.n_qtiles = (p.n_q + kBM - 1) / kBM;
-  const int n_wt = (p.n_q + 31) / 32;
-  p.wt_base = n_wt / p.n_qtiles;
-  p.wt_rem = n_wt % p.n_qtiles;
-  p.total_work = p.n_qtiles * p.n_heads;
-  p.work_per_xcd = (p.total_work + 7) / 8;
-  constexpr size_t lds_bytes = 2 * kRing * kTileBytes;
-  // The kernel needs more dynamic LDS than the default limit; the limit is raised once per
-  // device (the attribute belongs to the device that is current when it is set).
-  constexpr int kMaxDevices = 64;
-  static std::once_flag attr_once[kMaxDevices];
-  static hipError_t attr_status[kMaxDevices];
+// Combines the partial results of every query tile whose keys were split over several workgroups:
+// with m_p the running maximum of piece p (its shift, negated) and m the largest of them,
+//   O = sum_p 2^((m_p - m) scale*log2e) O_p,   l = sum_p 2^((m_p - m) scale*log2e) l_p,
+// which is the same softmax as one pass over all keys (the factors only re-base the exponentials).
+// One workgroup per query tile, threads laid out as in the attention kernel.
+__global__ __launch_bounds__(512) void block_attn_merge_kernel(const AttnParams p) {
+  const int hq = blockIdx.x;
+  const int w_first = ix::first_wg_of(hq, p.n_tiles, p.units), w_last = ix::last_wg_of(hq, p.n_tiles, p.units);
+  if (w_first == w_last) return;  // one workgroup had all the keys and stored the rows itself
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hh = lane >> 5;
+  const int per_item = p.n_heads * p.n_qtiles;
+  const int item = hq / per_item;
+  const int head = (hq - item * per_item) / p.n_qtiles;
+  const int qt = hq - item * per_item - head * p.n_qtiles;
+  if (wave >= ix::wave_tiles_of_qtile(qt, p.wt_base, p.wt_rem)) return;
+  const int q_row = (ix::first_wave_tile_of_qtile(qt, p.wt_base, p.wt_rem) + wave) * 32 + (lane & 31);
+  auto part_of = [&](int w) {
+    return p.partials + static_cast<int64_t>(ix::partial_slot(hq, w)) * sdvg::kPartialFloats + wave * (66 * 64) + lane;
+  };
+  float shift_min = part_of(w_first)[65 * 64];
+  for (int w = w_first + 1; w <= w_last; ++w) shift_min = fminf(shift_min, part_of(w)[65 * 64]);
+  f32x16 o_acc[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[u][i] = 0.f;
+  float l_run = 0.f;
+  for (int w = w_first; w <= w_last; ++w) {
+    const float *part = part_of(w);
+    const float f = __builtin_amdgcn_exp2f((shift_min - part[65 * 64]) * p.scale_log2e);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o_acc[u][i] += f * part[(16 * u + i) * 64];
+    l_run += f * part[64 * 64];
+  }
+  const float inv_l = 1.0f / lane_sum32(l_run);
+  const sdvg::AttnItem it = kernarg_items()[item];
+  store_rows(p, it, head, q_row, hh, o_acc, inv_l);
+}
+
+// Per-device facts the launcher needs, fetched once per device: the kernel's dynamic-LDS limit
+// has to be raised (the attribute belongs to the device that is current when it is set), and the
+// key split is sized by the number of compute units.
+constexpr int kMaxDevices = 64;
+struct DeviceInfo {
+  hipError_t status = hipSuccess;
+  int n_cu = 0;
+};
+int device_info(const DeviceInfo **out) {
+  static std::once_flag once[kMaxDevices];
+  static DeviceInfo info[kMaxDevices];
   int dev = 0;
   SDVG_HIP_CHECK(hipGetDevice(&dev));
   if (dev < 0 || dev >= kMaxDevices) return SDVG_ERR_UNSUPPORTED;
-  std::call_once(attr_once[dev], [dev] {
-    attr_status[dev] = hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  std::call_once(once[dev], [dev] {
+    constexpr size_t lds_bytes = 2 * kRing * kTileBytes;
+    DeviceInfo &d = info[dev];
+    d.status = hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (d.status == hipSuccess)
+      d.status = hipFuncSetAttribute(reinterpret_cast<const void *>(block_attn_bf16_kernel<true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (d.status == hipSuccess)
+      d.status = hipDeviceGetAttribute(&d.n_cu, hipDeviceAttributeMultiprocessorCount, dev);
   });
-  SDVG_HIP_CHECK(attr_status[dev]);
-  hipLaunchKernelGGL(block_attn_bf16_kernel, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes, s, p);
-  SDVG_HIP_CHECK(hipGetLastError());
+  SDVG_HIP_CHECK(info[dev].status);
+  *out = &info[dev];
   return SDVG_OK;
 }
 
-}  // namespace
+// How a launch is cut into workgroups. Plain: one workgroup per query tile (units == n_tiles).
+// Key split: when the query tiles would leave a good part of the last round of workgroups idle
+// (a drafter-shaped layer has 12 heads x 19 query tiles = 228 workgroups for 256 compute units),
+// the (query tile, key tile) pairs are dealt out evenly over whole rounds instead, every
+// workgroup taking the same number of pairs; query tiles cut by a workgroup boundary leave
+// partial results that a second, small kernel merges.
+struct Plan {
+  int n_qtiles, n_hq, n_tiles, units, total_wg;
+  int64_t workspace_bytes;  // 0 when nothing is split
+};
+Plan make_plan(int n_items, int n_q, int n_heads, int64_t n_k, int n_cu, int split_mode) {
+  Plan pl;
+  pl.n_qtiles = (n_q + kBM - 1) / kBM;
+  pl.n_hq = n_items * n_heads * pl.n_qtiles;
+  pl.n_tiles = static_cast<int>((n_k + kBN - 1) / kBN);
+  pl.units = pl.n_tiles;
+  pl.total_wg = pl.n_hq;
+  pl.workspace_bytes = 0;
+  if (split_mode == SDVG_SPLIT_NEVER || n_cu <= 0) return pl;
+  const int rounds = (pl.n_hq + n_cu - 1) / n_cu;
+  const double idle = 1.0 - static_cast<double>(pl.n_hq) / (static_cast<double>(rounds) * n_cu);
+  // The split costs a second kernel, the partial results' traffic and a slower main kernel, and
+  // a chip that is only partly busy clocks higher. Measured on MI355X (4680 queries): 12 heads
+  // (11 % of the compute units idle) 15 % slower split than plain; 5 heads (63 % idle) 4 % faster;
+  // 2 heads (85 % idle) 83 % faster. SDVG_SPLIT_AUTO therefore splits from 60 % idle on.
+  if (pl.n_hq % n_cu == 0 || rounds > 4 || pl.n_tiles < 32) return pl;
+  if (split_mode == SDVG_SPLIT_AUTO && idle < 0.6) return pl;
+  const int64_t all = static_cast<int64_t>(pl.n_hq) * pl.n_tiles;
+  const int64_t wgs = static_cast<int64_t>(rounds) * n_cu;
+  pl.units = static_cast<int>((all + wgs - 1) / wgs);  // <= n_tiles, because wgs >= n_hq
+  if (pl.units < 16) return Plan{pl.n_qtiles, pl.n_hq, pl.n_tiles, pl.n_tiles, pl.n_hq, 0};
+  pl.total_wg = static_cast<int>((all + pl.units - 1) / pl.units);
+  pl.workspace_bytes = static_cast<int64_t>(pl.n_hq + pl.total_wg) * sdvg::kPartialFloats * 4;
+  return pl;
+}
 
-extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cache,
-                               const void *v_cache, const void *k_blk, const void *v_blk,
-                               int64_t cache_len, void *out, void *stream) {
-  if (!desc || !q || !k_blk || !v_blk || !out) return SDVG_ERR_NULL;
+int launch_bf16(const AttnParams &p_in, const Plan &pl, hipStream_t s) {
+  AttnParams p = p_in;
+  p.n_qtiles = pl.n_qtiles;
+  p.n_hq = pl.n_hq;
+  p.n_tiles = pl.n_tiles;
+  p.units = pl.units;
+  p.total_work = pl.total_wg;
+  p.work_per_xcd = (p.total_work + 7) / 8;
+  const int n_wt = (p.n_q + 31) / 32;
+  p.wt_base = n_wt / p.n_qtiles;
+  p.wt_rem = n_wt % p.n_qtiles;
+  constexpr size_t lds_bytes = 2 * kRing * kTileBytes;
+  if (p.units == p.n_tiles)
+    hipLaunchKernelGGL(block_attn_bf16_kernel<false>, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes, s, p);
+  else
+    hipLaunchKernelGGL(block_attn_bf16_kernel<true>, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes, s, p);
+  SDVG_HIP_CHECK(hipGetLastError());
+  if (p.units != p.n_tiles) {
+    hipLaunchKernelGGL(block_attn_merge_kernel, dim3(p.n_hq), dim3(512), 0, s, p);
+    SDVG_HIP_CHECK(hipGetLastError());
+  }
+  return SDVG_OK;
+}
+
+// Host-side validation shared by the entry points; fills the shape part of the parameters.
+int check_desc(const sdvg_attn_desc *desc, int64_t cache_len, AttnParams &p) {
+  if (!desc) return SDVG_ERR_NULL;
   if (desc->head_dim != 128) return SDVG_ERR_UNSUPPORTED;
   if (desc->dtype != SDVG_BF16 && desc->dtype != SDVG_F32) return SDVG_ERR_UNSUPPORTED;
   if (desc->n_q < 1 || desc->n_blk < 1 || desc->n_heads < 1) return SDVG_ERR_SHAPE;
   if (cache_len < 0 || cache_len + desc->n_blk > INT32_MAX) return SDVG_ERR_RANGE;
-  if (cache_len > 0 && (!k_cache || !v_cache)) return SDVG_ERR_NULL;
   // scale == 0 selects the models' default 1/sqrt(head_dim); anything else must be finite and > 0
   if (!(desc->scale >= 0.f) || !isfinite(desc->scale)) return SDVG_ERR_RANGE;
   const float scale = desc->scale == 0.f ? 1.0f / sqrtf(static_cast<float>(desc->head_dim)) : desc->scale;
@@ -584,19 +735,7 @@ extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const 
     if ((desc->kv_token_stride | desc->kv_head_stride) & 7) return SDVG_ERR_ALIGN;
     if (desc->kv_token_stride >= (int64_t{1} << 30) || desc->kv_head_stride >= (int64_t{1} << 30))
       return SDVG_ERR_UNSUPPORTED;
-    if (!sdvg::aligned16(k_cache) || !sdvg::aligned16(v_cache)) return SDVG_ERR_ALIGN;
   }
-  if (!sdvg::aligned16(q) || !sdvg::aligned16(k_blk) || !sdvg::aligned16(v_blk) ||
-      !sdvg::aligned16(out))
-    return SDVG_ERR_ALIGN;
-
-  AttnParams p{};
-  p.q = q;
-  p.k_cache = k_cache;
-  p.v_cache = v_cache;
-  p.k_blk = k_blk;
-  p.v_blk = v_blk;
-  p.out = out;
   p.q_ts = desc->q_token_stride;
   p.q_hs = desc->q_head_stride;
   p.o_ts = desc->o_token_stride;
@@ -610,6 +749,93 @@ extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const 
   p.n_k = static_cast<int32_t>(cache_len + desc->n_blk);
   p.n_heads = desc->n_heads;
   p.scale_log2e = scale * 1.4426950408889634f;
-  if (desc->dtype == SDVG_F32) return sdvg::launch_block_attn_f32(p, static_cast<hipStream_t>(stream));
-  return launch_bf16(p, static_cast<hipStream_t>(stream));
+  return SDVG_OK;
+}
+
+int check_item(const sdvg::AttnItem &it, int64_t cache_len) {
+  if (!it.q || !it.k_blk || !it.v_blk || !it.out) return SDVG_ERR_NULL;
+  if (cache_len > 0 && (!it.k_cache || !it.v_cache)) return SDVG_ERR_NULL;
+  if (cache_len > 0 && (!sdvg::aligned16(it.k_cache) || !sdvg::aligned16(it.v_cache))) return SDVG_ERR_ALIGN;
+  if (!sdvg::aligned16(it.q) || !sdvg::aligned16(it.k_blk) || !sdvg::aligned16(it.v_blk) ||
+      !sdvg::aligned16(it.out))
+    return SDVG_ERR_ALIGN;
+  return SDVG_OK;
+}
+
+// Common path of the batched entry points: `workspace` null means no key split.
+int attn_batch(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q, const void *const *k_cache,
+               const void *const *v_cache, const void *const *k_blk, const void *const *v_blk,
+               int64_t cache_len, void *const *out, void *workspace, int64_t workspace_bytes,
+               int32_t split_mode, bool own_workspace, void *stream) {
+  AttnParams p{};
+  if (!desc || !q || !k_blk || !v_blk || !out) return SDVG_ERR_NULL;
+  if (n_items < 1 || n_items > sdvg::kMaxAttnItems) return SDVG_ERR_SHAPE;
+  if (split_mode < SDVG_SPLIT_NEVER || split_mode > SDVG_SPLIT_ALWAYS) return SDVG_ERR_UNSUPPORTED;
+  int st = check_desc(desc, cache_len, p);
+  if (st != SDVG_OK) return st;
+  if (cache_len > 0 && (!k_cache || !v_cache)) return SDVG_ERR_NULL;
+  for (int i = 0; i < n_items; ++i) {
+    p.items[i] = sdvg::AttnItem{q[i], cache_len > 0 ? k_cache[i] : nullptr, cache_len > 0 ? v_cache[i] : nullptr,
+                                k_blk[i], v_blk[i], out[i]};
+    st = check_item(p.items[i], cache_len);
+    if (st != SDVG_OK) return st;
+  }
+  p.n_items = n_items;
+  if (desc->dtype == SDVG_F32) {  // check path: one plain launch per item
+    for (int i = 0; i < n_items; ++i) {
+      AttnParams one = p;
+      one.items[0] = p.items[i];
+      one.n_items = 1;
+      st = sdvg::launch_block_attn_f32(one, static_cast<hipStream_t>(stream));
+      if (st != SDVG_OK) return st;
+    }
+    return SDVG_OK;
+  }
+  if (workspace && !sdvg::aligned16(workspace)) return SDVG_ERR_ALIGN;
+  const DeviceInfo *dev = nullptr;
+  st = device_info(&dev);
+  if (st != SDVG_OK) return st;
+  Plan pl = make_plan(n_items, p.n_q, p.n_heads, p.n_k, dev->n_cu, workspace ? split_mode : SDVG_SPLIT_NEVER);
+  if (pl.workspace_bytes > workspace_bytes) {
+    // the split does not fit the workspace: an error for the entry point that owns its
+    // workspace (its size is a documented limit), otherwise the plain launch is always possible
+    if (own_workspace) return SDVG_ERR_RANGE;
+    pl = make_plan(n_items, p.n_q, p.n_heads, p.n_k, dev->n_cu, SDVG_SPLIT_NEVER);
+  }
+  p.partials = static_cast<float *>(workspace);
+  return launch_bf16(p, pl, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cache,
+                               const void *v_cache, const void *k_blk, const void *v_blk,
+                               int64_t cache_len, void *out, void *stream) {
+  if (!desc || !q || !k_blk || !v_blk || !out) return SDVG_ERR_NULL;
+  return attn_batch(desc, 1, &q, &k_cache, &v_cache, &k_blk, &v_blk, cache_len, &out, nullptr, 0, SDVG_SPLIT_NEVER,
+                    false, stream);
+}
+
+extern "C" int sdvg_block_attn_batch(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q,
+                                     const void *const *k_cache, const void *const *v_cache,
+                                     const void *const *k_blk, const void *const *v_blk, int64_t cache_len,
+                                     void *const *out, void *workspace, int64_t workspace_bytes,
+                                     int32_t split_mode, void *stream) {
+  if (workspace_bytes < 0) return SDVG_ERR_SHAPE;
+  return attn_batch(desc, n_items, q, k_cache, v_cache, k_blk, v_blk, cache_len, out, workspace,
+                    workspace ? workspace_bytes : 0, split_mode, false, stream);
+}
+
+extern "C" int64_t sdvg_block_attn_workspace_bytes(const sdvg_attn_desc *desc, int32_t n_items, int64_t cache_len,
+                                                   int32_t split_mode) {
+  AttnParams p{};
+  if (n_items < 1 || n_items > sdvg::kMaxAttnItems) return SDVG_ERR_SHAPE;
+  if (split_mode < SDVG_SPLIT_NEVER || split_mode > SDVG_SPLIT_ALWAYS) return SDVG_ERR_UNSUPPORTED;
+  int st = check_desc(desc, cache_len, p);
+  if (st != SDVG_OK) return st;
+  if (desc->dtype != SDVG_BF16) return 0;
+  const DeviceInfo *dev = nullptr;
+  st = device_info(&dev);
+  if (st != SDVG_OK) return st;
+  return make_plan(n_items, p.n_q, p.n_heads, p.n_k, dev->n_cu, split_mode).workspace_bytes;
 }

@@ -39,12 +39,12 @@ __global__ __launch_bounds__(kThreads) void block_attn_f32_kernel(const sdvg::At
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r32 = lane & 31, hh = lane >> 5;
 
-  const float *q = static_cast<const float *>(p.q);
-  const float *k_cache = static_cast<const float *>(p.k_cache);
-  const float *v_cache = static_cast<const float *>(p.v_cache);
-  const float *k_blk = static_cast<const float *>(p.k_blk);
-  const float *v_blk = static_cast<const float *>(p.v_blk);
-  float *out = static_cast<float *>(p.out);
+  const float *q = static_cast<const float *>(p.items[0].q);
+  const float *k_cache = static_cast<const float *>(p.items[0].k_cache);
+  const float *v_cache = static_cast<const float *>(p.items[0].v_cache);
+  const float *k_blk = static_cast<const float *>(p.items[0].k_blk);
+  const float *v_blk = static_cast<const float *>(p.items[0].v_blk);
+  float *out = static_cast<float *>(p.items[0].out);
 
   // Q fragments: B operand of S^T = K Q^T; lane holds Q[q_row][2*s + hh], s = 0..63
   const int q_row = qt * kBM + wave * 32 + r32;

@@ -36,9 +36,13 @@ struct Streams {
   int c_len, n_k;  // cached tokens; cached + block tokens
 };
 
-// Tile numbers at which the plain "64 tokens further" copy step stops being right.
+// Tile numbers at which the plain "64 tokens further" copy step stops being right. A workgroup
+// walks a SEGMENT [t_first, t_end) of the key tiles (the whole range 0 .. n_tiles unless the
+// keys of a query tile are split over several workgroups); tile numbers are absolute.
 struct Geometry {
   int n_tiles;    // ceil(n_k / 64)
+  int t_first;    // first tile of the segment
+  int t_end;      // one past the last tile of the segment
   int t_seam_lo;  // first tile that holds a block token
   int t_seam_hi;  // first tile wholly inside the block
   int t_ragged;   // first tile with a row past the last key (== n_tiles if none)
@@ -46,15 +50,17 @@ struct Geometry {
   uint64_t step_c, step_b;  // 64 tokens of the cache / of the block, in bytes
 };
 
-SDVG_HD Geometry make_geometry(const Streams &s) {
+SDVG_HD Geometry make_geometry(const Streams &s, int t_first, int t_end) {
   Geometry g;
   g.n_tiles = (s.n_k + kBN - 1) / kBN;
+  g.t_first = t_first;
+  g.t_end = t_end;
   g.t_seam_lo = s.c_len / kBN;
   g.t_seam_hi = (s.c_len + kBN - 1) / kBN;
   g.t_ragged = s.n_k / kBN;
   g.g_lo = g.t_seam_lo - kAhead;
   g.g_hi = g.t_seam_hi - kAhead;
-  g.g_end = (g.t_ragged < g.n_tiles ? g.t_ragged : g.n_tiles) - kAhead;
+  g.g_end = (g.t_ragged < g.t_end ? g.t_ragged : g.t_end) - kAhead;
   g.step_c = static_cast<uint64_t>(kBN) * s.kv_tsb;
   g.step_b = static_cast<uint64_t>(kBN) * s.blk_tsb;
   return g;
@@ -95,11 +101,11 @@ SDVG_HD void step_ptrs(RowPtrs &r, uint64_t step) {
   r.v[1] += step;
 }
 
-// Prologue (tiles 0, 1, 2 in order): the seam tiles, the first tile wholly in the block and the
-// ragged last tile recompute the pointers; every other tile is one 64-token step from its
-// predecessor. Returns true if the pointers were recomputed.
+// Prologue (the segment's first three tiles in order): the first tile, the seam tiles, the first
+// tile wholly in the block and the ragged last tile compute the pointers from scratch; every
+// other tile is one 64-token step from its predecessor.
 SDVG_HD bool tile_is_special(const Geometry &g, int t) {
-  return t == 0 || static_cast<unsigned>(t - g.t_seam_lo) <= static_cast<unsigned>(g.t_seam_hi - g.t_seam_lo) ||
+  return t == g.t_first || static_cast<unsigned>(t - g.t_seam_lo) <= static_cast<unsigned>(g.t_seam_hi - g.t_seam_lo) ||
          t >= g.t_ragged;
 }
 
@@ -114,7 +120,7 @@ SDVG_HD uint32_t copy_dst(int slot, int wave, int i) {
 // tokens on. That is wrong when tile t + kAhead holds the cache/block seam, is the first tile
 // wholly inside the block, is the ragged last tile, or does not exist; for those t (the
 // "events") the pointers are set beforehand so that the step lands on the right rows (past the
-// end: on the last tile again, a harmless redundant copy). next_event(x) is the first event at or
+// end of the segment: on its last tile again, a harmless redundant copy). next_event(x) is the first event at or
 // after tile x.
 SDVG_HD int next_event(const Geometry &g, int x) {
   if (x >= g.g_lo && x <= g.g_hi) return x;
@@ -122,7 +128,9 @@ SDVG_HD int next_event(const Geometry &g, int x) {
   return (x < g.g_lo && g.g_lo < e) ? g.g_lo : e;
 }
 
-SDVG_HD uint64_t first_fast_step(const Geometry &g) { return kAhead < g.t_seam_lo ? g.step_c : g.step_b; }
+SDVG_HD uint64_t first_fast_step(const Geometry &g) {
+  return g.t_first + kAhead < g.t_seam_lo ? g.step_c : g.step_b;
+}
 
 struct Cursor {
   RowPtrs ptrs;
@@ -132,8 +140,8 @@ struct Cursor {
 };
 
 SDVG_HD void on_event(const Streams &s, const Geometry &g, int t, int wave, int lane, Cursor &c) {
-  const int tau = t + kAhead < g.n_tiles ? t + kAhead : g.n_tiles - 1;
-  c.fast_step = t + kAhead >= g.n_tiles ? 0 : (tau + 1 < g.t_seam_lo ? g.step_c : g.step_b);
+  const int tau = t + kAhead < g.t_end ? t + kAhead : g.t_end - 1;
+  c.fast_step = t + kAhead >= g.t_end ? 0 : (tau + 1 < g.t_seam_lo ? g.step_c : g.step_b);
   row_ptrs(s, tau, 0, wave, lane, c.ptrs);
   row_ptrs(s, tau, 1, wave, lane, c.ptrs);
   c.ptrs.k[0] -= c.fast_step;
@@ -158,6 +166,36 @@ SDVG_HD int v_read_offset(int lane, int j, int db, int hi) {
   const int i16 = lane & 15, b16 = (lane >> 4) & 1, hh = lane >> 5;
   return (16 * j + 8 * hi + 4 * hh + (i16 >> 2)) * 256 + ((db ^ (i16 >> 2)) * 64) + 32 * b16 + 8 * (i16 & 3);
 }
+
+// ---- key split. The (query tile, key tile) pairs of a launch are numbered hq * n_tiles + t and
+// cut into runs of `units` pairs, one run per workgroup, so that a workgroup may finish one
+// query tile's keys and begin the next one's: every workgroup then has the same amount of work
+// even when the query tiles do not fill the chip's compute units evenly. units == n_tiles is the
+// plain case (one workgroup per query tile). A query tile whose keys are spread over several
+// workgroups gets one partial result per workgroup, in slot hq + w of the partial buffer
+// (distinct for distinct (hq, w): along the runs either hq or w grows from one piece to the next).
+struct Piece {
+  int hq;        // query tile (item, head, q-tile flattened)
+  int t_first, t_end;  // its key tiles handled here
+  bool whole;    // the piece covers all key tiles: the result is final, no partial is written
+};
+SDVG_HD Piece piece_at(int64_t u, int64_t u_end, int n_tiles) {
+  Piece pc;
+  pc.hq = static_cast<int>(u / n_tiles);
+  pc.t_first = static_cast<int>(u - static_cast<int64_t>(pc.hq) * n_tiles);
+  const int64_t left = u_end - u;
+  pc.t_end = left < n_tiles - pc.t_first ? pc.t_first + static_cast<int>(left) : n_tiles;
+  pc.whole = pc.t_first == 0 && pc.t_end == n_tiles;
+  return pc;
+}
+// First and last workgroup that hold a piece of query tile hq.
+SDVG_HD int first_wg_of(int hq, int n_tiles, int units) {
+  return static_cast<int>(static_cast<int64_t>(hq) * n_tiles / units);
+}
+SDVG_HD int last_wg_of(int hq, int n_tiles, int units) {
+  return static_cast<int>((static_cast<int64_t>(hq + 1) * n_tiles - 1) / units);
+}
+SDVG_HD int partial_slot(int hq, int wg) { return hq + wg; }
 
 // ---- work distribution. Workgroups are dealt round-robin to the 8 XCDs; giving XCD x the
 // contiguous range [x * work_per_xcd, (x + 1) * work_per_xcd) of (head, q-tile) work keeps the

@@ -76,8 +76,8 @@ bool run_copies(const ix::Streams &s, int n_blk, int slot, int t, const ix::Curs
   return true;
 }
 
-bool check_tile(const ix::Streams &s, const Lds &lds, int is_v, int tile, Failure &f) {
-  const int slot = tile % ix::kRing;
+bool check_tile(const ix::Streams &s, const Lds &lds, int is_v, int tile, int t_first, Failure &f) {
+  const int slot = (tile - t_first) % ix::kRing;
   for (int row = 0; row < ix::kBN; ++row)
     for (int pc = 0; pc < 16; ++pc) {
       const Cell &c = lds.cell[is_v][slot][row][pc];
@@ -90,7 +90,8 @@ bool check_tile(const ix::Streams &s, const Lds &lds, int is_v, int tile, Failur
   return true;
 }
 
-bool replay(int c_len, int n_blk, uint32_t kv_tsb, uint32_t blk_tsb, Failure &f) {
+// Replays the piece [t_first, t_end) of the key tiles (the whole range when t_end < 0).
+bool replay(int c_len, int n_blk, uint32_t kv_tsb, uint32_t blk_tsb, Failure &f, int t_first = 0, int t_end = -1) {
   ix::Streams s;
   s.kc = kBase;
   s.vc = kBase + kSpan;
@@ -100,13 +101,15 @@ bool replay(int c_len, int n_blk, uint32_t kv_tsb, uint32_t blk_tsb, Failure &f)
   s.blk_tsb = blk_tsb;
   s.c_len = c_len;
   s.n_k = c_len + n_blk;
-  const ix::Geometry g = ix::make_geometry(s);
+  const int n_tiles_all = (c_len + n_blk + ix::kBN - 1) / ix::kBN;
+  if (t_end < 0) t_end = n_tiles_all;
+  const ix::Geometry g = ix::make_geometry(s, t_first, t_end);
   static thread_local Lds lds;
   lds = Lds();
   static thread_local ix::Cursor cur[ix::kWaves][64];
 
-  // prologue: tiles 0..2
-  for (int t = 0; t < 3 && t < g.n_tiles; ++t) {
+  // prologue: the piece's first three tiles into ring slots 0..2
+  for (int t = t_first; t < t_first + 3 && t < t_end; ++t) {
     for (int w = 0; w < ix::kWaves; ++w)
       for (int lane = 0; lane < 64; ++lane) {
         if (ix::tile_is_special(g, t)) {
@@ -116,38 +119,39 @@ bool replay(int c_len, int n_blk, uint32_t kv_tsb, uint32_t blk_tsb, Failure &f)
           ix::step_ptrs(cur[w][lane].ptrs, t < g.t_seam_lo ? g.step_c : g.step_b);
         }
       }
-    if (!run_copies(s, n_blk, t, t, cur, lds, f)) return false;
+    if (!run_copies(s, n_blk, t - t_first, t, cur, lds, f)) return false;
   }
   for (int w = 0; w < ix::kWaves; ++w)
     for (int lane = 0; lane < 64; ++lane) {
       cur[w][lane].fast_step = ix::first_fast_step(g);
-      cur[w][lane].t_evt = ix::next_event(g, 0);
+      cur[w][lane].t_evt = ix::next_event(g, t_first);
       cur[w][lane].mask_next = false;
     }
-  if (!check_tile(s, lds, 0, 0, f)) return false;  // S(0) is computed in the prologue
+  if (!check_tile(s, lds, 0, t_first, t_first, f)) return false;  // S of the first tile is computed in the prologue
 
   bool masked_last = false;
-  for (int t = 0; t < g.n_tiles; ++t) {
+  for (int t = t_first; t < t_end; ++t) {
     // matrix phase of tile t: S(t+1) from K slot t+1 (meaningless after the last tile), PV from V slot t
-    if (t + 1 < g.n_tiles && !check_tile(s, lds, 0, t + 1, f)) return false;
-    if (!check_tile(s, lds, 1, t, f)) return false;
+    if (t + 1 < t_end && !check_tile(s, lds, 0, t + 1, t_first, f)) return false;
+    if (!check_tile(s, lds, 1, t, t_first, f)) return false;
     for (int w = 0; w < ix::kWaves; ++w)
       for (int lane = 0; lane < 64; ++lane) {
         ix::Cursor &c = cur[w][lane];
         if (t == c.t_evt) ix::on_event(s, g, t, w, lane, c);
         ix::step_ptrs(c.ptrs, c.fast_step);
       }
-    if (!run_copies(s, n_blk, (t + ix::kAhead) % ix::kRing, t, cur, lds, f)) return false;
+    if (!run_copies(s, n_blk, (t - t_first + ix::kAhead) % ix::kRing, t, cur, lds, f)) return false;
     // the tail mask is asked for exactly when the scores of the ragged last tile are produced
     const bool want_mask = t + 1 == g.n_tiles - 1 && s.n_k % ix::kBN != 0;
     for (int w = 0; w < ix::kWaves; ++w)
-      if (cur[w][0].mask_next != want_mask && t + 1 < g.n_tiles) {
+      if (cur[w][0].mask_next != want_mask && t + 1 < t_end) {
         f = {"tail mask flag wrong", t, w, 0, cur[w][0].mask_next, want_mask};
         return false;
       }
     masked_last |= want_mask;
   }
-  if (g.n_tiles > 1 && (s.n_k % ix::kBN != 0) != masked_last) {
+  // (when the ragged tile is the piece's FIRST tile the kernel masks it in its prologue instead)
+  if (t_end == g.n_tiles && t_end - t_first > 1 && (s.n_k % ix::kBN != 0) != masked_last) {
     f = {"ragged last tile never masked", g.n_tiles - 1, 0, 0, 0, 0};
     return false;
   }
@@ -216,6 +220,52 @@ bool check_work_split(Failure &f) {
   return true;
 }
 
+// Cutting the (query tile, key tile) pairs into runs: the pieces of all workgroups tile the pair
+// space exactly once, a query tile's pieces lie in workgroups first_wg_of .. last_wg_of, and no
+// two pieces share a partial slot.
+bool check_key_split(Failure &f) {
+  for (int n_hq : {1, 5, 228, 456})
+    for (int n_tiles : {1, 3, 37, 220, 512})
+      for (int units : {1, 2, 7, 36, 37, 196, 219, 220, 512}) {
+        if (units > n_tiles) continue;
+        const int64_t all = static_cast<int64_t>(n_hq) * n_tiles;
+        const int n_wg = static_cast<int>((all + units - 1) / units);
+        std::vector<char> seen(all, 0);
+        std::vector<char> slot_used(n_hq + n_wg, 0);
+        for (int w = 0; w < n_wg; ++w) {
+          int64_t u = static_cast<int64_t>(w) * units;
+          const int64_t u_end = u + units < all ? u + units : all;
+          int pieces = 0;
+          while (u < u_end) {
+            const ix::Piece pc = ix::piece_at(u, u_end, n_tiles);
+            const bool ok = pc.hq >= 0 && pc.hq < n_hq && pc.t_first >= 0 && pc.t_end > pc.t_first &&
+                            pc.t_end <= n_tiles && pc.whole == (pc.t_first == 0 && pc.t_end == n_tiles) &&
+                            w >= ix::first_wg_of(pc.hq, n_tiles, units) && w <= ix::last_wg_of(pc.hq, n_tiles, units) &&
+                            (pc.whole == (ix::first_wg_of(pc.hq, n_tiles, units) == ix::last_wg_of(pc.hq, n_tiles, units)));
+            if (!ok || slot_used[ix::partial_slot(pc.hq, w)]++) {
+              f = {"key split: bad piece or slot used twice", n_hq, n_tiles, units, w, pc.hq};
+              return false;
+            }
+            for (int t = pc.t_first; t < pc.t_end; ++t)
+              if (seen[static_cast<int64_t>(pc.hq) * n_tiles + t]++) {
+                f = {"key split: pair handled twice", n_hq, n_tiles, units, w, t};
+                return false;
+              }
+            u += pc.t_end - pc.t_first;
+            ++pieces;
+          }
+          (void)pieces;
+        }
+        for (int64_t i = 0; i < all; ++i)
+          if (!seen[i]) {
+            f = {"key split: pair never handled", n_hq, n_tiles, units, static_cast<int>(i / n_tiles),
+                 static_cast<int>(i % n_tiles)};
+            return false;
+          }
+      }
+  return true;
+}
+
 int report(const Failure &f, int c_len, int n_blk) {
   std::printf("FAIL c_len=%d n_blk=%d: %s (t=%d, %d, %d, %d, %d)\n", c_len, n_blk, f.what, f.t, f.wave, f.lane, f.a,
               f.b);
@@ -234,6 +284,7 @@ int main(int argc, char **argv) {
   }
   if (!check_read_side(f)) return report(f, -1, -1);
   if (!check_work_split(f)) return report(f, -1, -1);
+  if (!check_key_split(f)) return report(f, -1, -1);
   long n_cfg = 0;
   int bad = 0;
   // dense range: every residue of c_len and n_blk modulo the tile, up to several tiles of each;
@@ -260,6 +311,21 @@ int main(int argc, char **argv) {
       ++n_cfg;
     }
   }
+  // pieces of the key range, as the key split hands them to workgroups: every start / end
+  // around the seam and the ragged end, short pieces (shorter than the ring) included
+  for (int c : {0, 1, 64, 100, 200, 4680, 9360})
+    for (int n : {1, 70, 312, 4680}) {
+      const int nt = (c + n + ix::kBN - 1) / ix::kBN;
+      for (int a = 0; a < nt; a += (nt > 40 ? 7 : 1))
+        for (int len : {1, 2, 3, 4, 5, 9, 64, 196}) {
+          const int b = a + len < nt ? a + len : nt;
+          if (!replay(c, n, 12 * 256, 40 * 256, f, a, b)) {
+            std::printf("piece [%d, %d): ", a, b);
+            return report(f, c, n);
+          }
+          ++n_cfg;
+        }
+    }
   std::printf("ok: %ld configurations\n", n_cfg);
   return 0;
 }

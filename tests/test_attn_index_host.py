@@ -31,8 +31,8 @@ def test_copy_schedule_delivers_the_concatenation(tmp_path):
 
 MUTANTS = [
     ("event one tile late", "- kAhead;\n  g.step_c", "- kAhead + 1;\n  g.step_c"),
-    ("block pitch used for the first cache steps", "return kAhead < g.t_seam_lo ? g.step_c : g.step_b;",
-     "return kAhead < g.t_seam_lo ? g.step_b : g.step_c;"),
+    ("block pitch used for the first cache steps", "return g.t_first + kAhead < g.t_seam_lo ? g.step_c : g.step_b;",
+     "return g.t_first + kAhead < g.t_seam_lo ? g.step_b : g.step_c;"),
     ("second half of a wave's rows lands in the wrong place", "(i & 1) * 8 * 1024", "(i & 1) * 4 * 1024"),
     ("one pointer not re-based at an event", "  c.ptrs.v[1] -= c.fast_step;\n", ""),
     ("K swizzle dropped on the copy side", "+ row_off + (ld_p ^ (row & 15)) * 16;", "+ row_off + ld_p * 16;"),
@@ -40,6 +40,10 @@ MUTANTS = [
     ("block rows addressed with the cache pitch", "* (in_cache ? s.kv_tsb : s.blk_tsb);", "* s.kv_tsb;"),
     ("seam row taken from the cache", "const bool in_cache = j < s.c_len;", "const bool in_cache = j <= s.c_len;"),
     ("V read offset without the swizzle", "((db ^ (i16 >> 2)) * 64)", "(db * 64)"),
+    ("piece start ignored when the first events are looked up", "g.g_end = (g.t_ragged < g.t_end ? g.t_ragged : g.t_end) - kAhead;",
+     "g.g_end = (g.t_ragged < g.n_tiles ? g.t_ragged : g.n_tiles) - kAhead;"),
+    ("a piece cut at the wrong tile", "pc.t_end = left < n_tiles - pc.t_first ? pc.t_first + static_cast<int>(left) : n_tiles;",
+     "pc.t_end = left < n_tiles - pc.t_first ? pc.t_first + static_cast<int>(left) + 1 : n_tiles;"),
     ("first event missed", "if (x >= g.g_lo && x <= g.g_hi) return x;", "if (x > g.g_lo && x <= g.g_hi) return x;"),
 ]
 
