@@ -131,6 +131,25 @@ int sdvg_block_attn_batch(const sdvg_attn_desc *desc, int32_t n_items, const voi
                           int32_t split_mode, void *stream);
 
 /*
+ * sdvg_block_attn_batch for callers that cannot allocate device memory or provide a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same
+ * arguments, results and errors, but the partial results of a key split go to a fixed 64 MiB
+ * array inside the library's device image (sdvg_block_attn_static_workspace_limit() bytes,
+ * held by every GPU the library runs on until the process ends) instead of caller memory.
+ * The call allocates nothing and frees nothing. A shape whose split needs more than the array
+ * holds returns SDVG_ERR_RANGE (nothing is launched); sdvg_block_attn_workspace_bytes tells the
+ * need beforehand, and SDVG_SPLIT_NEVER needs none. Every call on a GPU uses that GPU's one
+ * array: calls that overlap in time on one GPU (different streams or threads) race -- serialise
+ * them, or use sdvg_block_attn_batch with workspaces of their own. Nothing in the array has to
+ * be cleared between calls: each call writes every partial result it later reads.
+ */
+int sdvg_block_attn_batch_static(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q,
+                                 const void *const *k_cache, const void *const *v_cache,
+                                 const void *const *k_blk, const void *const *v_blk, int64_t cache_len,
+                                 void *const *out, int32_t split_mode, void *stream);
+int64_t sdvg_block_attn_static_workspace_limit(void);
+
+/*
  * Bytes of workspace with which sdvg_block_attn_batch would split keys for this shape and
  * split_mode on the current device; 0 if it would not split (then no workspace is needed).
  * Negative sdvg_status on a bad descriptor.

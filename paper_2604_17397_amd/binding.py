@@ -60,6 +60,10 @@ def lib():
         L.sdvg_block_attn_batch.restype = ctypes.c_int
         L.sdvg_block_attn_batch.argtypes = [ctypes.POINTER(sdvg_attn_desc), i32, pp, pp, pp, pp, pp, i64, pp,
                                             vp, i64, i32, vp]
+        L.sdvg_block_attn_batch_static.restype = ctypes.c_int
+        L.sdvg_block_attn_batch_static.argtypes = [ctypes.POINTER(sdvg_attn_desc), i32, pp, pp, pp, pp, pp, i64, pp,
+                                                   i32, vp]
+        L.sdvg_block_attn_static_workspace_limit.restype = ctypes.c_int64
         L.sdvg_block_attn_workspace_bytes.restype = ctypes.c_int64
         L.sdvg_block_attn_workspace_bytes.argtypes = [ctypes.POINTER(sdvg_attn_desc), i32, i64, i32]
         L.sdvg_kv_commit.restype = ctypes.c_int
@@ -197,8 +201,16 @@ def block_attn_workspace_bytes(q, k_cache, v_cache, k_blk, v_blk, cache_len, n_i
     return int(n)
 
 
+def block_attn_batch_static(qs, k_caches, v_caches, k_blks, v_blks, cache_len, outs, split="auto", scale=None,
+                            stream=None):
+    """sdvg_block_attn_batch_static: as block_attn_batch, with the library's fixed workspace. `outs`
+    is required (this entry point is for callers that do not allocate)."""
+    return block_attn_batch(qs, k_caches, v_caches, k_blks, v_blks, cache_len, outs=outs, split=split, scale=scale,
+                            stream=stream, _static=True)
+
+
 def block_attn_batch(qs, k_caches, v_caches, k_blks, v_blks, cache_len, outs=None, workspace=None,
-                     split="auto", scale=None, stream=None):
+                     split="auto", scale=None, stream=None, _static=False):
     """sdvg_block_attn_batch: lists of n tensors each (k_caches / v_caches may be None when
     cache_len == 0); every item must have the same shapes and strides. `workspace`: optional
     device tensor (any dtype) the library may use to split keys over workgroups, under the policy
@@ -226,11 +238,16 @@ def block_attn_batch(qs, k_caches, v_caches, k_blks, v_blks, cache_len, outs=Non
         if not workspace.is_contiguous() or workspace.device != qs[0].device:
             raise ValueError("workspace must be a contiguous tensor on the items' device")
         ws_ptr, ws_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
-    st = lib().sdvg_block_attn_batch(ctypes.byref(descs[0]), n, arr(qs), arr(k_caches), arr(v_caches),
-                                     arr(k_blks), arr(v_blks), cache_len, arr(outs), ws_ptr, ws_bytes,
-                                     _SPLIT[split], _stream_ptr(stream))
+    if _static:
+        st = lib().sdvg_block_attn_batch_static(ctypes.byref(descs[0]), n, arr(qs), arr(k_caches), arr(v_caches),
+                                                arr(k_blks), arr(v_blks), cache_len, arr(outs), _SPLIT[split],
+                                                _stream_ptr(stream))
+    else:
+        st = lib().sdvg_block_attn_batch(ctypes.byref(descs[0]), n, arr(qs), arr(k_caches), arr(v_caches),
+                                         arr(k_blks), arr(v_blks), cache_len, arr(outs), ws_ptr, ws_bytes,
+                                         _SPLIT[split], _stream_ptr(stream))
     if st != 0:
-        raise SdvgError(st, "sdvg_block_attn_batch")
+        raise SdvgError(st, "sdvg_block_attn_batch_static" if _static else "sdvg_block_attn_batch")
     return outs
 
 

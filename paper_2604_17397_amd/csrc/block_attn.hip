@@ -623,6 +623,16 @@ __global__ __launch_bounds__(512) void block_attn_merge_kernel(const AttnParams 
   store_rows(p, it, head, q_row, hh, o_acc, inv_l);
 }
 
+// Workspace of sdvg_block_attn_batch_static, the entry point that may not allocate: the partial
+// results of a key split live in this array instead of in caller memory. Every device the
+// library runs on holds its own copy, at its own address, until the process ends; host code
+// never uses the array's name as an address, only the per-device pointer hipGetSymbolAddress
+// returned (DeviceInfo::scratch). 64 MiB = 496 partial results of 256 rows x 128 floats (+ row
+// sums and shifts): enough for every split of up to 240 query tiles over one round of 256
+// workgroups (a 12-head drafter layer needs 484).
+constexpr int64_t kScratchBytes = int64_t{64} << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 // Per-device facts the launcher needs, fetched once per device: the kernel's dynamic-LDS limit
 // has to be raised (the attribute belongs to the device that is current when it is set), and the
 // key split is sized by the number of compute units.
@@ -630,6 +640,7 @@ constexpr int kMaxDevices = 64;
 struct DeviceInfo {
   hipError_t status = hipSuccess;
   int n_cu = 0;
+  void *scratch = nullptr;  // this device's copy of the static workspace
 };
 int device_info(const DeviceInfo **out) {
   static std::once_flag once[kMaxDevices];
@@ -647,6 +658,7 @@ int device_info(const DeviceInfo **out) {
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (d.status == hipSuccess)
       d.status = hipDeviceGetAttribute(&d.n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (d.status == hipSuccess) d.status = hipGetSymbolAddress(&d.scratch, HIP_SYMBOL(scratch));
   });
   SDVG_HIP_CHECK(info[dev].status);
   *out = &info[dev];
@@ -795,6 +807,10 @@ int attn_batch(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q
   const DeviceInfo *dev = nullptr;
   st = device_info(&dev);
   if (st != SDVG_OK) return st;
+  if (own_workspace) {
+    workspace = dev->scratch;
+    workspace_bytes = kScratchBytes;
+  }
   Plan pl = make_plan(n_items, p.n_q, p.n_heads, p.n_k, dev->n_cu, workspace ? split_mode : SDVG_SPLIT_NEVER);
   if (pl.workspace_bytes > workspace_bytes) {
     // the split does not fit the workspace: an error for the entry point that owns its
@@ -825,6 +841,17 @@ extern "C" int sdvg_block_attn_batch(const sdvg_attn_desc *desc, int32_t n_items
   return attn_batch(desc, n_items, q, k_cache, v_cache, k_blk, v_blk, cache_len, out, workspace,
                     workspace ? workspace_bytes : 0, split_mode, false, stream);
 }
+
+extern "C" int sdvg_block_attn_batch_static(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q,
+                                            const void *const *k_cache, const void *const *v_cache,
+                                            const void *const *k_blk, const void *const *v_blk,
+                                            int64_t cache_len, void *const *out, int32_t split_mode,
+                                            void *stream) {
+  return attn_batch(desc, n_items, q, k_cache, v_cache, k_blk, v_blk, cache_len, out, nullptr, 0, split_mode, true,
+                    stream);
+}
+
+extern "C" int64_t sdvg_block_attn_static_workspace_limit(void) { return kScratchBytes; }
 
 extern "C" int64_t sdvg_block_attn_workspace_bytes(const sdvg_attn_desc *desc, int32_t n_items, int64_t cache_len,
                                                    int32_t split_mode) {
