@@ -12,7 +12,13 @@ Prints ONE JSON line. `value` is whole-step throughput in attention TFLOP/s (alg
 FLOPs 4*n_q*n_k*d*H per call over the full step time, router/commit/rollback included).
 `roofline` is the attention kernel against the bf16 dense MFMA peak, from HIP-event timing of
 the launches inside the timed region; `hbm_kernels` gives commit/rollback GB/s the same way.
-`cpu_baseline` times the fp64 oracle on a bounded row sample of the same workload.
+After the timed region (nothing below touches `value` or `roofline.achieved`) the line also
+reports, under `other_shapes`: the drafter-shaped layer (plain, key-split, two items per launch),
+the target-shaped layer with two items per launch, attention by cache length (0..8 cached
+blocks), and the 7-block streaming aggregate at both shapes; and `cpu_baseline`: the fp64 oracle
+timed on a bounded row sample of the same workload, with the GPU's rows checked on it, plus the
+oracle's nested-loop commit on a slice. The run exits non-zero if the sampled parity breaks the
+stated bounds.
 """
 import argparse
 import json
@@ -26,10 +32,18 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this workload and
-# scaled by what the same counters read for the commit kernel, a plain copy of known size
-# (FETCH_SIZE reads half the known bytes, WRITE_SIZE all of them). Only valid for the target workload.
-TRAFFIC_TARGET = {"block_attn": 0.9875e9 + 0.0479e9, "kv_commit": 2 * 3.834e9, "kv_rollback": 3.835e9}
+BF16_MAX_ABS, BF16_REL_RMS = 2e-2, 1e-2   # parity bounds of the bf16 attention path
+# HBM bytes per launch of the target workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this file; written next to the counter summaries, with the commit and commands that made them.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_target_traffic.json")
+
+
+def load_traffic():
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return None
 
 
 def main():
@@ -39,9 +53,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="target", choices=["target", "drafter", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-shapes", action="store_true",
+                    help="skip the untimed extra measurements (profiling runs)")
     ap.add_argument("--denoise-steps", type=int, default=4)
-    ap.add_argument("--sweep", action="store_true",
-                    help="also time attention at 0..8 cached blocks (adds launches of other shapes)")
+    ap.add_argument("--input-std", type=float, default=1.0,
+                    help="standard deviation of the synthetic q/k/v (1 = the workload's N(0,1)); the "
+                         "attention rate depends on the operand values through the chip's power management")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by heads with no exchange "
@@ -64,6 +81,12 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    def normal(shape, tid, seed=si.SEED):
+        t = si.device_normal_bf16(shape, seed, tid, device=dev)
+        if args.input_std != 1.0:
+            t.mul_(args.input_std)
+        return t
+
     cfg = si.CONFIGS[args.workload]
     H, T, L, D = cfg["n_heads"], cfg["block_tokens"], cfg["n_layers"], cfg["head_dim"]
     nb = cfg["cached_blocks"]
@@ -72,12 +95,12 @@ def main():
     n_k = c_len + T
     cap = (nb + 1) * T
 
-    k_all = si.device_normal_bf16((L, cap, H, D), si.SEED, si.TID_K_CACHE, device=dev)
-    v_all = si.device_normal_bf16((L, cap, H, D), si.SEED, si.TID_V_CACHE, device=dev)
+    k_all = normal((L, cap, H, D), si.TID_K_CACHE)
+    v_all = normal((L, cap, H, D), si.TID_V_CACHE)
     cache = P.KVCache(k_all, v_all, T, cache_len=c_len)
-    k_blk = si.device_normal_bf16((L, T, H, D), si.SEED, si.TID_K_BLK, device=dev)
-    v_blk = si.device_normal_bf16((L, T, H, D), si.SEED, si.TID_V_BLK, device=dev)
-    q = si.device_normal_bf16((T, H, D), si.SEED, si.TID_Q, device=dev)
+    k_blk = normal((L, T, H, D), si.TID_K_BLK)
+    v_blk = normal((L, T, H, D), si.TID_V_BLK)
+    q = normal((T, H, D), si.TID_Q)
     out = torch.empty_like(q)
     n_rounds = args.steps + args.warmup
     scores = torch.from_numpy(si.frame_scores_correlated(si.SEED, n_rounds)).to(dev)
@@ -130,6 +153,14 @@ def main():
     commit_gbps = 2 * payload / (commit_ms * 1e-3) / 1e9
     rollback_gbps = payload / (rollback_ms * 1e-3) / 1e9
 
+    traffic = load_traffic() if args.workload == "target" else None
+
+    def traffic_of(kernel):
+        if not traffic or kernel not in traffic.get("kernels", {}):
+            return None
+        k = traffic["kernels"][kernel]
+        return k["fetch_bytes"] + k["write_bytes"]
+
     line = {
         "metric": "block-attn TFLOP/s & % bf16 MFMA peak at 14B shape; KV-commit GB/s",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -139,58 +170,106 @@ def main():
                                "(cache %d + block %d), %d denoising steps, then route + commit + rollback"
                                % (args.workload, L, H, D, T, n_k, c_len, T, S),
                    "attn_calls_per_step": S * L, "attn_flops_per_call": flops_call,
-                   "commit_payload_bytes": payload, "tau": tau},
+                   "commit_payload_bytes": payload, "tau": tau, "input_std": args.input_std},
         "roofline": {"kernel": "block_attn_bf16_kernel", "bound": "mfma",
                      "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": TRAFFIC_TARGET["block_attn"] if args.workload == "target" else None,
+                     "traffic": traffic_of("block_attn"),
+                     "traffic_source": (None if not traffic else
+                                        "profiles/bench_target_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                        "runs of this file at commit %s, not this run)" % traffic.get("commit")),
                      "avg_launch_ms": round(attn_ms, 4),
                      "median_launch_ms": round(per_step_attn[len(per_step_attn) // 2], 4),
                      "min_launch_ms": round(per_step_attn[0], 4)},
         "hbm_kernels": {
             "kv_commit": {"bound": "hbm", "achieved": round(commit_gbps, 1), "peak": PEAK_HBM_GBPS,
                           "unit": "GB/s", "frac": round(commit_gbps / PEAK_HBM_GBPS, 4),
-                          "bytes": 2 * payload, "ms": round(commit_ms, 4),
-                          "traffic": TRAFFIC_TARGET["kv_commit"] if args.workload == "target" else None},
+                          "bytes": 2 * payload, "ms": round(commit_ms, 4), "traffic": traffic_of("kv_commit")},
             "kv_rollback": {"bound": "hbm", "achieved": round(rollback_gbps, 1), "peak": PEAK_HBM_GBPS,
                             "unit": "GB/s", "frac": round(rollback_gbps / PEAK_HBM_GBPS, 4),
-                            "bytes": payload, "ms": round(rollback_ms, 4),
-                            "traffic": TRAFFIC_TARGET["kv_rollback"] if args.workload == "target" else None},
+                            "bytes": payload, "ms": round(rollback_ms, 4), "traffic": traffic_of("kv_rollback")},
             "route_us": round(route_us, 1)},
         "accepted_blocks": int(accepted),
     }
 
-    # attention rate against the cache length, up to the paper's 9-block protocol (8 cached blocks)
-    if args.sweep:
-        sw_k = si.device_normal_bf16((8 * T, H, D), si.SEED, si.TID_K_CACHE + 50, device=dev)
-        sw_v = si.device_normal_bf16((8 * T, H, D), si.SEED, si.TID_V_CACHE + 50, device=dev)
-        sweep = []
-        for kb_ in range(9):
-            c_ = kb_ * T
-            P.block_attn(q, sw_k, sw_v, k_blk[0], v_blk[0], c_, out=out)
-            torch.cuda.synchronize()
-            we = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            we[0].record()
-            for _ in range(10):
-                P.block_attn(q, sw_k, sw_v, k_blk[0], v_blk[0], c_, out=out)
-            we[1].record()
-            torch.cuda.synchronize()
-            sweep.append(round(si.attn_flops(T, c_ + T, H, D) / (we[0].elapsed_time(we[1]) / 10 * 1e-3) / 1e12, 1))
-        line["roofline"]["tflops_by_cached_blocks_0_to_8"] = sweep
-        del sw_k, sw_v
+    def time_calls(fn, n):
+        fn()
+        torch.cuda.synchronize()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        for _ in range(n):
+            fn()
+        e[1].record()
+        torch.cuda.synchronize()
+        return e[0].elapsed_time(e[1]) / n
+
+    def rate(flops, ms):
+        t = flops / (ms * 1e-3) / 1e12
+        return {"tflops": round(t, 1), "frac": round(t / PEAK_BF16_TFLOPS, 4), "ms": round(ms, 4)}
+
+    if not args.no_other_shapes and args.workload == "target":
+        other = {}
+        # -- the target layer with two items per launch (conditional + unconditional pass)
+        q2, out2 = normal((T, H, D), si.TID_Q, seed=si.SEED + 1), torch.empty_like(q)
+        kc0, vc0 = cache.layer(0)
+        kc1, vc1 = cache.layer(1)
+        ms = time_calls(lambda: P.block_attn_batch([q, q2], [kc0, kc1], [vc0, vc1], [k_blk[0], k_blk[1]],
+                                                   [v_blk[0], v_blk[1]], c_len, outs=[out, out2]), 10)
+        other["target_two_items_per_launch"] = rate(2 * flops_call, ms)
+        # -- attention against the cache length, up to the paper's 9-block protocol (8 cached blocks)
+        sw_k = normal((8 * T, H, D), si.TID_K_CACHE + 50)
+        sw_v = normal((8 * T, H, D), si.TID_V_CACHE + 50)
+        other["target_tflops_by_cached_blocks_0_to_8"] = [
+            round(si.attn_flops(T, kb_ * T + T, H, D) /
+                  (time_calls(lambda: P.block_attn(q, sw_k, sw_v, k_blk[0], v_blk[0], kb_ * T, out=out), 10) * 1e-3)
+                  / 1e12, 1) for kb_ in range(9)]
+        del sw_k, sw_v, q2, out2
+
+        # -- 7-block streaming generation, attention only: block k = 0..6 runs S x L calls at cache_len 4680 k
+        def streaming(Ls, Hs, kk, vv, kb_, vb_, qq, oo):
+            fl, ms_tot = 0.0, 0.0
+            for b in range(7):
+                def calls():
+                    for l in range(Ls):
+                        P.block_attn(qq, kk[l], vv[l], kb_[l], vb_[l], b * T, out=oo)
+                ms_tot += time_calls(calls, S) * S
+                fl += S * Ls * si.attn_flops(T, b * T + T, Hs, D)
+            return {"attention_tflop": round(fl / 1e12, 1), "seconds": round(ms_tot * 1e-3, 3),
+                    "tflops": round(fl / (ms_tot * 1e-3) / 1e12, 1),
+                    "frac": round(fl / (ms_tot * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        other["streaming_7_blocks"] = {"target": streaming(L, H, k_all, v_all, k_blk, v_blk, q, out)}
+
+        # -- the drafter-shaped layer (12 heads, 2 cached blocks) and the drafter's streaming run
+        dcfg = si.CONFIGS["drafter"]
+        Hd, Ld = dcfg["n_heads"], dcfg["n_layers"]
+        dk = normal((Ld, 7 * T, Hd, D), si.TID_K_CACHE + 60)
+        dv = normal((Ld, 7 * T, Hd, D), si.TID_V_CACHE + 60)
+        dkb = normal((Ld, T, Hd, D), si.TID_K_BLK + 60)
+        dvb = normal((Ld, T, Hd, D), si.TID_V_BLK + 60)
+        dq = normal((T, Hd, D), si.TID_Q + 60)
+        dq2 = normal((T, Hd, D), si.TID_Q + 61)
+        do, do2 = torch.empty_like(dq), torch.empty_like(dq)
+        dc = dcfg["cached_blocks"] * T
+        dflops = si.attn_flops(T, dc + T, Hd, D)
+        drafter = rate(dflops, time_calls(lambda: P.block_attn(dq, dk[0], dv[0], dkb[0], dvb[0], dc, out=do), 20))
+        need = P.block_attn_workspace_bytes(dq, dk[0], dv[0], dkb[0], dvb[0], dc, split="always")
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        drafter["key_split_forced"] = rate(dflops, time_calls(
+            lambda: P.block_attn_batch([dq], [dk[0]], [dv[0]], [dkb[0]], [dvb[0]], dc, outs=[do], workspace=ws,
+                                       split="always"), 20))
+        drafter["key_split_forced"]["workspace_bytes"] = need
+        drafter["two_items_per_launch"] = rate(2 * dflops, time_calls(
+            lambda: P.block_attn_batch([dq, dq2], [dk[0], dk[1]], [dv[0], dv[1]], [dkb[0], dkb[1]], [dvb[0], dvb[1]],
+                                       dc, outs=[do, do2]), 20))
+        other["drafter_layer_12_heads_4680x14040"] = drafter
+        other["streaming_7_blocks"]["drafter"] = streaming(Ld, Hd, dk, dv, dkb, dvb, dq, do)
+        del dk, dv, dkb, dvb, dq, dq2, do, do2, ws
+        line["other_shapes"] = other
 
     # snapshot / restore of an opaque buffer (1 GiB), outside the step: a next-row kernel
     snap_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     snap_dst = torch.empty_like(snap_src)
-    P.buffer_snapshot(snap_dst, snap_src)
-    torch.cuda.synchronize()
-    se = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    se[0].record()
-    for _ in range(5):
-        P.buffer_snapshot(snap_dst, snap_src)
-    se[1].record()
-    torch.cuda.synchronize()
-    snap_ms = se[0].elapsed_time(se[1]) / 5
+    snap_ms = time_calls(lambda: P.buffer_snapshot(snap_dst, snap_src), 5)
     snap_gbps = 2.0 * (1 << 30) / (snap_ms * 1e-3) / 1e9
     line["hbm_kernels"]["buffer_snapshot"] = {"bound": "hbm", "achieved": round(snap_gbps, 1), "peak": PEAK_HBM_GBPS,
                                               "unit": "GB/s", "frac": round(snap_gbps / PEAK_HBM_GBPS, 4),
@@ -211,13 +290,25 @@ def main():
         "clock_ghz": round(int(probe_cycles.item()) / (probe_ms * 1e-3) / 1e9, 3),
         "note": "register-only bf16 MFMA loop on the same chip; the 2500 peak assumes 2.4 GHz"}
 
+    parity_ok = True
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(np, torch, si, cache, q, k_blk, v_blk, c_len, out, P)
+        par = line["cpu_baseline"]["gpu_vs_oracle_on_sample"]
+        parity_ok = (par["max_abs_err"] <= BF16_MAX_ABS and par["rel_rms"] <= BF16_REL_RMS and
+                     par["worst_head_rel_rms"] <= BF16_REL_RMS)
+        par["within_bounds"] = parity_ok
     print(json.dumps(line))
+    if not parity_ok:
+        print("bench.py: the GPU rows disagree with the oracle beyond max|err| %.0e / rel-RMS %.0e"
+              % (BF16_MAX_ABS, BF16_REL_RMS), file=sys.stderr)
+        sys.exit(3)
 
 
 def cpu_baseline(np, torch, si, cache, q, k_blk, v_blk, c_len, out, P):
-    """Time the fp64 oracle on a bounded row sample of layer 0 and check the GPU rows on it."""
+    """Time the fp64 oracle on a bounded row sample of layer 0 and check the GPU rows on it; time
+    the oracle's nested-loop commit on a slice of the layers."""
+    from concurrent.futures import ThreadPoolExecutor
+
     import oracle
     from oracle import build as oracle_build
     oracle_build.build(force=False)
@@ -247,12 +338,42 @@ def cpu_baseline(np, torch, si, cache, q, k_blk, v_blk, c_len, out, P):
     flops = 4.0 * len(rows) * n_k * D * H
     g = si.bf16_bits_to_f64(hout[rows])
     err = g - ref
+    num, den = np.sum(err * err, axis=(0, 2)), np.sum(ref * ref, axis=(0, 2))
+    per_head = np.sqrt(num / den)
+
+    # the oracle's commit (nested loops over layer, token, head, dim) on a slice of the layers:
+    # one thread as it stands, then one such call per host thread on its own layer
+    Lc = min(4, k_blk.shape[0])
+    T = k_blk.shape[1]
+    blk_k, blk_v = bits(k_blk[:Lc]), bits(v_blk[:Lc])
+    slice_bytes = 2.0 * blk_k.nbytes                     # K and V of the slice
+    mirror = oracle.KVMirror(1, T, H, D, T)
+    t = time.perf_counter()
+    oracle.kv_commit(mirror, blk_k[:1], blk_v[:1], 0)
+    one_layer_s = time.perf_counter() - t
+    n_par = max(1, min(threads, os.cpu_count() or 1))
+    mirrors = [oracle.KVMirror(1, T, H, D, T) for _ in range(n_par)]
+    with ThreadPoolExecutor(n_par) as pool:
+        t = time.perf_counter()
+        list(pool.map(lambda i: oracle.kv_commit(mirrors[i], blk_k[i % Lc:i % Lc + 1], blk_v[i % Lc:i % Lc + 1], 0),
+                      range(n_par)))
+        par_s = time.perf_counter() - t
+    layer_bytes = slice_bytes / Lc
     return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": threads,
-            "kind": "oracle", "seconds": round(dt, 2),
+            "host_logical_cpus": os.cpu_count(), "kind": "oracle", "seconds": round(dt, 2),
             "sample": "%d of %d query rows x all %d heads of layer 0, all %d keys (fp64, OpenMP)"
                       % (len(rows), n_q, H, n_k),
             "gpu_vs_oracle_on_sample": {"max_abs_err": float(np.max(np.abs(err))),
-                                        "rel_rms": float(math.sqrt(np.sum(err * err) / np.sum(ref * ref)))}}
+                                        "rel_rms": float(math.sqrt(num.sum() / den.sum())),
+                                        "worst_head_rel_rms": float(per_head.max()),
+                                        "worst_head": int(per_head.argmax())},
+            "oracle_commit": {"sample": "K and V of one layer (%d tokens x %d heads x %d, %.1f MB payload) per call"
+                                        % (T, H, D, layer_bytes / 1e6),
+                              "one_thread_seconds": round(one_layer_s, 4),
+                              "one_thread_gbps": round(2 * layer_bytes / one_layer_s / 1e9, 3),
+                              "threads": n_par, "all_threads_seconds": round(par_s, 4),
+                              "all_threads_gbps": round(2 * layer_bytes * n_par / par_s / 1e9, 3),
+                              "note": "read + write bytes; the GPU commit moves 40 such layers per launch"}}
 
 
 if __name__ == "__main__":
