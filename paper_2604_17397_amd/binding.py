@@ -9,7 +9,9 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libsdvg.so")
+# SDVG_LIBRARY names another build of the same library (e.g. one with host sanitizers); there is
+# still no fallback: whatever path is named must exist.
+LIB_PATH = os.environ.get("SDVG_LIBRARY") or os.path.join(HERE, "libsdvg.so")
 
 SDVG_BF16, SDVG_F32 = 0, 1
 SDVG_SPLIT_NEVER, SDVG_SPLIT_AUTO, SDVG_SPLIT_ALWAYS = 0, 1, 2
