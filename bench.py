@@ -224,6 +224,23 @@ def main():
                   (time_calls(lambda: P.block_attn(q, sw_k, sw_v, k_blk[0], v_blk[0], kb_ * T, out=out), 10) * 1e-3)
                   / 1e12, 1) for kb_ in range(9)]
         del sw_k, sw_v, q2, out2
+        # -- the block's last denoising step with its commit: 40 attention launches then the commit
+        #    kernel, against 40 launches with the commit fused in (sdvg_block_attn_commit)
+        def last_step_separate():
+            for l in range(L):
+                kc_, vc_ = cache.layer(l)
+                P.block_attn(q, kc_, vc_, k_blk[l], v_blk[l], c_len, out=out)
+            P.kv_commit(cache, k_blk, v_blk, nb)
+            cache.c.cache_len = c_len            # (timing only: the slot is overwritten again next call)
+
+        def last_step_fused():
+            for l in range(L):
+                kc_, vc_ = cache.layer(l)
+                P.block_attn_commit(q, kc_, vc_, k_blk[l], v_blk[l], c_len, out=out)
+        ms_sep, ms_fus = time_calls(last_step_separate, 3), time_calls(last_step_fused, 3)
+        other["last_step_plus_commit_ms"] = {"separate": round(ms_sep, 3), "fused": round(ms_fus, 3),
+                                             "commit_hidden_ms": round(ms_sep - ms_fus, 3)}
+        P.kv_rollback(cache, c_len)              # scrub the slot the fused launches filled
 
         # -- 7-block streaming generation, attention only: block k = 0..6 runs S x L calls at cache_len 4680 k
         def streaming(Ls, Hs, kk, vv, kb_, vb_, qq, oo):

@@ -97,6 +97,25 @@ int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const void *k_cac
                     int64_t cache_len, void *out, void *stream);
 
 /*
+ * Attention with the commit fused in (paper Sec. 3 "Inference flow": the block the target keeps
+ * -- an accepted draft, or the target's own regeneration -- updates its KV cache): sdvg_block_attn
+ * for one layer (bf16 only), and in the same launch the block's K and V rows are copied into
+ * tokens [cache_len, cache_len + n_blk) of k_cache / v_cache (this layer's base pointers, which
+ * must have room for them), addressed with the descriptor's kv strides. Meant for the LAST
+ * denoising step of a block: the copy runs on compute units the attention leaves idle, so the
+ * block's commit costs no extra pass over memory. The attention result is bit-identical to
+ * sdvg_block_attn's; the copied rows are bit-exact. k_blk / v_blk must not overlap the
+ * destination rows (SDVG_ERR_RANGE). The cache length is the caller's to advance: after the
+ * call has been made for every layer, sdvg_kv_commit_mark(cache, slot) moves the descriptor's
+ * cache_len to (slot + 1) * T under the same append-only rule as sdvg_kv_commit, without
+ * touching device memory. Asynchronous on `stream`.
+ */
+int sdvg_block_attn_commit(const sdvg_attn_desc *desc, const void *q, void *k_cache, void *v_cache,
+                           const void *k_blk, const void *v_blk, int64_t cache_len, void *out,
+                           void *stream);
+int sdvg_kv_commit_mark(sdvg_kv_cache *cache, int32_t slot);
+
+/*
  * The same attention for up to 8 independent (q, cache, block, out) sets in ONE launch -- e.g. the
  * conditional and the unconditional pass of classifier-free guidance (paper Sec. 4.1 "Models":
  * guidance scale 3.0), which share shapes and cache length but have their own tensors. Result

@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     KVCache,
     block_attn,
     block_attn_batch,
+    block_attn_commit,
+    kv_commit_mark,
     block_attn_batch_static,
     block_attn_workspace_bytes,
     kv_commit,

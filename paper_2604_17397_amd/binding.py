@@ -58,6 +58,10 @@ def lib():
         vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
         L.sdvg_block_attn.restype = ctypes.c_int
         L.sdvg_block_attn.argtypes = [ctypes.POINTER(sdvg_attn_desc), vp, vp, vp, vp, vp, i64, vp, vp]
+        L.sdvg_block_attn_commit.restype = ctypes.c_int
+        L.sdvg_block_attn_commit.argtypes = [ctypes.POINTER(sdvg_attn_desc), vp, vp, vp, vp, vp, i64, vp, vp]
+        L.sdvg_kv_commit_mark.restype = ctypes.c_int
+        L.sdvg_kv_commit_mark.argtypes = [ctypes.POINTER(sdvg_kv_cache), i32]
         pp = ctypes.POINTER(ctypes.c_void_p)
         L.sdvg_block_attn_batch.restype = ctypes.c_int
         L.sdvg_block_attn_batch.argtypes = [ctypes.POINTER(sdvg_attn_desc), i32, pp, pp, pp, pp, pp, i64, pp,
@@ -186,6 +190,30 @@ def block_attn(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=Non
     if st != 0:
         raise SdvgError(st, "sdvg_block_attn")
     return out
+
+
+def block_attn_commit(q, k_cache, v_cache, k_blk, v_blk, cache_len, out=None, scale=None, stream=None):
+    """sdvg_block_attn_commit: block_attn for one layer that also copies k_blk / v_blk into tokens
+    [cache_len, cache_len + n_blk) of k_cache / v_cache (which must be long enough). Returns out."""
+    cache_len = int(cache_len)
+    if out is None:
+        out = torch.empty(q.shape, dtype=q.dtype, device=q.device)
+    if k_cache is None or v_cache is None:
+        raise ValueError("the fused commit needs the layer's cache tensors")
+    d = _attn_desc(q, k_cache, v_cache, k_blk, v_blk, cache_len, out, scale)
+    if cache_len + k_blk.shape[0] > k_cache.shape[0]:
+        raise ValueError("the cache has no room for the block after cache_len")
+    st = lib().sdvg_block_attn_commit(ctypes.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_blk),
+                                      _ptr(v_blk), cache_len, _ptr(out), _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_block_attn_commit")
+    return out
+
+
+def kv_commit_mark(cache, slot):
+    st = lib().sdvg_kv_commit_mark(ctypes.byref(cache.c), int(slot))
+    if st != 0:
+        raise SdvgError(st, "sdvg_kv_commit_mark")
 
 
 def _desc_key(d):

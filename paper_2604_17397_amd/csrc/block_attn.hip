@@ -134,6 +134,54 @@ __device__ __forceinline__ void store_rows(const AttnParams &p, const sdvg::Attn
   }
 }
 
+// Fused commit (paper Sec. 3 "Inference flow": the block the target keeps -- an accepted draft or
+// its own regeneration -- goes into the target's KV cache): workgroups appended to the attention
+// launch copy the block's K and V rows of this layer into cache tokens [cache_len, cache_len +
+// n_blk), 16 bytes per lane, while the attention workgroups (which only read tokens below
+// cache_len and the block itself) are still running. They are dispatched last and find their
+// compute units among those the last round of attention workgroups leaves idle.
+__device__ __forceinline__ void commit_block_rows(const AttnParams &p) {
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+  const sdvg::AttnItem it = kernarg_items()[0];
+  const int64_t chunks = static_cast<int64_t>(p.n_blk) * p.n_heads * 16;  // 16-byte chunks per tensor
+  const int64_t first = static_cast<int64_t>(blockIdx.x - p.copy_first_block) * 512 + threadIdx.x;
+  const int64_t stride = static_cast<int64_t>(p.n_copy_blocks) * 512;
+  auto locate = [&](int64_t g, const u32x4 *&src, u32x4 *&dst) __attribute__((always_inline)) {
+    const bool is_v = g >= chunks;
+    const int64_t c = is_v ? g - chunks : g;
+    const int64_t row = c >> 4;
+    const int ch = static_cast<int>(c & 15);
+    const int64_t tok = row / p.n_heads;
+    const int head = static_cast<int>(row - tok * p.n_heads);
+    src = reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(is_v ? it.v_blk : it.k_blk) + tok * p.blk_ts +
+                                          head * p.blk_hs + ch * 8);
+    dst = reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(is_v ? p.v_commit_dst : p.k_commit_dst) + tok * p.kv_ts +
+                                    head * p.kv_hs + ch * 8);
+  };
+  // four chunks in flight per lane: the few workgroups that do this have to stream by themselves
+  int64_t g = first;
+  for (; g + 3 * stride < 2 * chunks; g += 4 * stride) {
+    const u32x4 *s0, *s1, *s2, *s3;
+    u32x4 *d0, *d1, *d2, *d3;
+    locate(g, s0, d0);
+    locate(g + stride, s1, d1);
+    locate(g + 2 * stride, s2, d2);
+    locate(g + 3 * stride, s3, d3);
+    const u32x4 a = __builtin_nontemporal_load(s0), b = __builtin_nontemporal_load(s1),
+                c = __builtin_nontemporal_load(s2), d = __builtin_nontemporal_load(s3);
+    __builtin_nontemporal_store(a, d0);
+    __builtin_nontemporal_store(b, d1);
+    __builtin_nontemporal_store(c, d2);
+    __builtin_nontemporal_store(d, d3);
+  }
+  for (; g < 2 * chunks; g += stride) {
+    const u32x4 *s0;
+    u32x4 *d0;
+    locate(g, s0, d0);
+    __builtin_nontemporal_store(__builtin_nontemporal_load(s0), d0);
+  }
+}
+
 // kSplit = false: one piece per workgroup (one query tile with all its key tiles; the hot case).
 // kSplit = true: the workgroup's run may hold several pieces, taken in a loop.
 template <bool kSplit>
@@ -161,6 +209,10 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   // ---- this workgroup's run of (query tile, key tile) pairs (block_attn_index.h, "key split").
   // Normally the run is exactly one query tile with all its key tiles; when the keys are split it
   // may end one query tile and begin the next, and the loop below takes the pieces in turn.
+  if (!kSplit && static_cast<int>(blockIdx.x) >= p.copy_first_block) {
+    commit_block_rows(p);
+    return;
+  }
   const int work = ix::work_of_block(blockIdx.x, p.work_per_xcd);
   if (work >= p.total_work) return;
   int64_t u_next = static_cast<int64_t>(work) * p.units;
@@ -701,7 +753,7 @@ Plan make_plan(int n_items, int n_q, int n_heads, int64_t n_k, int n_cu, int spl
   return pl;
 }
 
-int launch_bf16(const AttnParams &p_in, const Plan &pl, hipStream_t s) {
+int launch_bf16(const AttnParams &p_in, const Plan &pl, int n_cu, hipStream_t s) {
   AttnParams p = p_in;
   p.n_qtiles = pl.n_qtiles;
   p.n_hq = pl.n_hq;
@@ -713,8 +765,14 @@ int launch_bf16(const AttnParams &p_in, const Plan &pl, hipStream_t s) {
   p.wt_base = n_wt / p.n_qtiles;
   p.wt_rem = n_wt % p.n_qtiles;
   constexpr size_t lds_bytes = 2 * kRing * kTileBytes;
+  p.copy_first_block = 8 * p.work_per_xcd;
+  // Fused commit: as many copying workgroups as the last round of attention workgroups leaves
+  // compute units idle (they then run beside it for its whole length); a full round otherwise.
+  const int idle_cus = n_cu > 0 && p.total_work % n_cu ? n_cu - p.total_work % n_cu : 0;
+  p.n_copy_blocks = !p.k_commit_dst ? 0 : (idle_cus >= 4 ? idle_cus : (n_cu > 0 ? n_cu : 256));
   if (p.units == p.n_tiles)
-    hipLaunchKernelGGL(block_attn_bf16_kernel<false>, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes, s, p);
+    hipLaunchKernelGGL(block_attn_bf16_kernel<false>, dim3(8 * p.work_per_xcd + p.n_copy_blocks), dim3(512),
+                       lds_bytes, s, p);
   else
     hipLaunchKernelGGL(block_attn_bf16_kernel<true>, dim3(8 * p.work_per_xcd), dim3(512), lds_bytes, s, p);
   SDVG_HIP_CHECK(hipGetLastError());
@@ -758,6 +816,7 @@ int check_desc(const sdvg_attn_desc *desc, int64_t cache_len, AttnParams &p) {
   p.blk_hs = desc->blk_head_stride;
   p.cache_len = cache_len;
   p.n_q = desc->n_q;
+  p.n_blk = desc->n_blk;
   p.n_k = static_cast<int32_t>(cache_len + desc->n_blk);
   p.n_heads = desc->n_heads;
   p.scale_log2e = scale * 1.4426950408889634f;
@@ -819,7 +878,7 @@ int attn_batch(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q
     pl = make_plan(n_items, p.n_q, p.n_heads, p.n_k, dev->n_cu, SDVG_SPLIT_NEVER);
   }
   p.partials = static_cast<float *>(workspace);
-  return launch_bf16(p, pl, static_cast<hipStream_t>(stream));
+  return launch_bf16(p, pl, dev->n_cu, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -830,6 +889,41 @@ extern "C" int sdvg_block_attn(const sdvg_attn_desc *desc, const void *q, const 
   if (!desc || !q || !k_blk || !v_blk || !out) return SDVG_ERR_NULL;
   return attn_batch(desc, 1, &q, &k_cache, &v_cache, &k_blk, &v_blk, cache_len, &out, nullptr, 0, SDVG_SPLIT_NEVER,
                     false, stream);
+}
+
+extern "C" int sdvg_block_attn_commit(const sdvg_attn_desc *desc, const void *q, void *k_cache, void *v_cache,
+                                      const void *k_blk, const void *v_blk, int64_t cache_len, void *out,
+                                      void *stream) {
+  AttnParams p{};
+  if (!desc || !q || !k_blk || !v_blk || !out || !k_cache || !v_cache) return SDVG_ERR_NULL;
+  if (desc->dtype != SDVG_BF16) return SDVG_ERR_UNSUPPORTED;
+  int st = check_desc(desc, cache_len, p);
+  if (st != SDVG_OK) return st;
+  // the destination rows are addressed with the cache strides even when cache_len == 0
+  if (desc->kv_token_stride < 128 || desc->kv_head_stride < 128) return SDVG_ERR_SHAPE;
+  if ((desc->kv_token_stride | desc->kv_head_stride) & 7) return SDVG_ERR_ALIGN;
+  if (desc->kv_token_stride >= (int64_t{1} << 30) || desc->kv_head_stride >= (int64_t{1} << 30))
+    return SDVG_ERR_UNSUPPORTED;
+  if (!sdvg::aligned16(k_cache) || !sdvg::aligned16(v_cache)) return SDVG_ERR_ALIGN;
+  p.items[0] = sdvg::AttnItem{q, k_cache, v_cache, k_blk, v_blk, out};
+  st = check_item(p.items[0], cache_len);
+  if (st != SDVG_OK) return st;
+  p.n_items = 1;
+  p.k_commit_dst = static_cast<uint16_t *>(k_cache) + cache_len * desc->kv_token_stride;
+  p.v_commit_dst = static_cast<uint16_t *>(v_cache) + cache_len * desc->kv_token_stride;
+  // the block must not overlap the rows it is copied into
+  const int64_t dst_bytes = ((desc->n_blk - 1) * desc->kv_token_stride + (desc->n_heads - 1) * desc->kv_head_stride + 128) * 2;
+  const int64_t src_bytes = ((desc->n_blk - 1) * desc->blk_token_stride + (desc->n_heads - 1) * desc->blk_head_stride + 128) * 2;
+  for (const void *src : {k_blk, v_blk})
+    for (const void *dst : {static_cast<const void *>(p.k_commit_dst), static_cast<const void *>(p.v_commit_dst)}) {
+      const uintptr_t a = reinterpret_cast<uintptr_t>(src), b = reinterpret_cast<uintptr_t>(dst);
+      if (a < b + static_cast<uintptr_t>(dst_bytes) && b < a + static_cast<uintptr_t>(src_bytes)) return SDVG_ERR_RANGE;
+    }
+  const DeviceInfo *dev = nullptr;
+  st = device_info(&dev);
+  if (st != SDVG_OK) return st;
+  const Plan pl = make_plan(1, p.n_q, p.n_heads, p.n_k, dev->n_cu, SDVG_SPLIT_NEVER);
+  return launch_bf16(p, pl, dev->n_cu, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int sdvg_block_attn_batch(const sdvg_attn_desc *desc, int32_t n_items, const void *const *q,

@@ -17,6 +17,9 @@ struct AttnParams {
   int64_t q_ts, q_hs, o_ts, o_hs, kv_ts, kv_hs, blk_ts, blk_hs;  // strides in elements
   int64_t cache_len;
   float *partials;    // partial results of query tiles whose keys are split over workgroups (or null)
+  // fused commit: workgroups past the attention work copy item 0's block into these rows (or null)
+  void *k_commit_dst, *v_commit_dst;
+  int32_t n_blk, copy_first_block, n_copy_blocks;
   int32_t n_items, n_q, n_k, n_heads, n_qtiles;
   int32_t n_hq;       // query tiles of the launch: n_items * n_heads * n_qtiles
   int32_t n_tiles;    // key tiles: ceil(n_k / 64)

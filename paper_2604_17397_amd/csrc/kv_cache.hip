@@ -179,6 +179,15 @@ extern "C" int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const voi
   return SDVG_OK;
 }
 
+extern "C" int sdvg_kv_commit_mark(sdvg_kv_cache *cache, int32_t slot) {
+  int st = validate_cache(cache);
+  if (st != SDVG_OK) return st;
+  const int64_t T = cache->block_tokens;
+  if (slot < 0 || slot * T != cache->cache_len || (slot + 1) * T > cache->capacity_tokens) return SDVG_ERR_RANGE;
+  cache->cache_len = (slot + 1) * T;
+  return SDVG_OK;
+}
+
 extern "C" int sdvg_kv_rollback(sdvg_kv_cache *cache, int64_t new_len, void *stream) {
   int st = validate_cache(cache);
   if (st != SDVG_OK) return st;
