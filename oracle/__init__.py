@@ -8,6 +8,7 @@ from .oracle import (  # noqa: F401
     kv_rollback,
     buffer_copy,
     route,
+    rope,
     num_threads,
     KVMirror,
 )

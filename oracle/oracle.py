@@ -36,6 +36,8 @@ def _lib():
         lib.sdvg_oracle_buffer_copy.argtypes = [vp, vp, i64]
         lib.sdvg_oracle_route.restype = ctypes.c_int
         lib.sdvg_oracle_route.argtypes = [vp, i64, ctypes.c_float, i64, ctypes.c_int, vp]
+        lib.sdvg_oracle_rope.restype = ctypes.c_int
+        lib.sdvg_oracle_rope.argtypes = [vp, vp, vp, vp, i64, i64, i64]
         lib.sdvg_oracle_num_threads.restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -154,3 +156,20 @@ def route(scores, tau, block_idx, mode="min"):
     dec = _lib().sdvg_oracle_route(s.ctypes.data, s.size, ctypes.c_float(tau), int(block_idx),
                                    {"min": 0, "mean": 1}[mode], qb.ctypes.data)
     return int(dec), qb[0]
+
+
+def rope(x, cos, sin):
+    """Rotary embedding of bf16 rows x [tokens, heads, dim] (uint16 bit patterns) by the angles
+    whose cosines / sines are given per (token, pair): cos, sin float32 [tokens, dim // 2].
+    Returns uint16 bit patterns of the same shape."""
+    assert x.dtype == np.uint16 and x.ndim == 3
+    x = np.ascontiguousarray(x)
+    n, H, d = x.shape
+    cos = np.ascontiguousarray(cos, dtype=np.float32)
+    sin = np.ascontiguousarray(sin, dtype=np.float32)
+    assert cos.shape == (n, d // 2) and sin.shape == (n, d // 2)
+    out = np.empty_like(x)
+    rc = _lib().sdvg_oracle_rope(x.ctypes.data, cos.ctypes.data, sin.ctypes.data, out.ctypes.data, n, H, d)
+    if rc != 0:
+        raise RuntimeError("sdvg_oracle_rope failed: %d" % rc)
+    return out

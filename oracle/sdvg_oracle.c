@@ -16,6 +16,8 @@
  *     of the ablation (Sec. 4.3 "Min-frame vs. average-frame scoring").
  *   - snapshot / restore of an opaque buffer: Sec. 3 "Inference flow" (VAE decode cache cloned
  *     before scoring, restored on rejection): a byte copy.
+ *   - rotary position embedding of q / k rows: Sec. 4.1 "Models" (KV caching "via RoPE positional
+ *     embeddings"; the paper prints no formula -- the reading taken is at the function).
  *
  * Everything is fp64, two-pass, materialised-row: deliberately NOT tiled / online.
  * Element types: 0 = bfloat16 bit patterns (uint16), 1 = float32. Both widen exactly to fp64.
@@ -214,6 +216,46 @@ int sdvg_oracle_route(const float *scores, int64_t n_frames, float tau, int64_t 
 int sdvg_oracle_buffer_copy(uint8_t *dst, const uint8_t *src, int64_t n_bytes) {
   if (n_bytes < 0) return -2;
   for (int64_t i = 0; i < n_bytes; ++i) dst[i] = src[i];
+  return 0;
+}
+
+/*
+ * Rotary position embedding (paper Sec. 4.1 "Models" names RoPE and nothing more). Reading taken:
+ * the standard rotation of consecutive pairs -- element 2i and 2i+1 of a head's vector are the
+ * real and imaginary part of a complex number that is multiplied by exp(i * angle) -- with the
+ * angle of (token, pair) supplied by the caller as tables cos[token][head_dim/2] and
+ * sin[token][head_dim/2] (fp32), so that any position scheme (1-D, or the 3-D frame/row/column
+ * scheme of video transformers) is the caller's choice and not part of this function.
+ * Input and output are bf16 bit patterns, dense [n_tokens][n_heads][head_dim]. The arithmetic is
+ * the kernel's precision, fp32, in a fixed order, because the result is rounded to bf16 and both
+ * sides must take that rounding decision from the same fp32 value:
+ *     re' = fma(re, cos, -(im * sin)),   im' = fma(re, sin, im * cos),
+ * each product and each fma rounded once to fp32, then round-to-nearest-even to bf16.
+ * Returns 0, or -2 on a bad shape.
+ */
+static uint16_t bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x0040u); /* NaN */
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+int sdvg_oracle_rope(const uint16_t *x, const float *cos_t, const float *sin_t, uint16_t *out,
+                     int64_t n_tokens, int64_t n_heads, int64_t head_dim) {
+  if (n_tokens < 0 || n_heads <= 0 || head_dim <= 0 || (head_dim & 1)) return -2;
+  const int64_t half = head_dim / 2;
+  for (int64_t t = 0; t < n_tokens; ++t)
+    for (int64_t h = 0; h < n_heads; ++h)
+      for (int64_t i = 0; i < half; ++i) {
+        const int64_t e = (t * n_heads + h) * head_dim + 2 * i;
+        const float re = (float)widen(x, e, ORACLE_BF16), im = (float)widen(x, e + 1, ORACLE_BF16);
+        const float c = cos_t[t * half + i], sn = sin_t[t * half + i];
+        const volatile float im_sin = im * sn; /* volatile: each product is rounded to fp32 on its own */
+        const volatile float im_cos = im * c;
+        out[e] = bf16_rne(fmaf(re, c, -im_sin));
+        out[e + 1] = bf16_rne(fmaf(re, sn, im_cos));
+      }
   return 0;
 }
 

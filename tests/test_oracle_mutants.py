@@ -14,6 +14,7 @@ from oracle import build as oracle_build
 
 import test_oracle_attn as pins_attn
 import test_oracle_kv_route as pins_kv
+import test_oracle_rope as pins_rope
 
 SRC = open(oracle_build.SRC).read()
 
@@ -46,6 +47,14 @@ ROUTE_PINS = [
     pins_kv.test_mean_route_of_opposite_infinities_is_the_canonical_nan,
 ]
 
+ROPE_PINS = [
+    pins_rope.test_zero_angle_is_the_identity_and_quarter_turn_swaps_the_pair,
+    pins_rope.test_matches_complex_multiplication_in_float64,
+    pins_rope.test_norm_is_preserved_and_rotations_compose,
+    pins_rope.test_relative_position_property,
+    pins_rope.test_worked_example_by_hand,
+]
+
 # (name, text to find (must occur exactly `count` times), replacement, which occurrence, pins)
 MUTANTS = [
     ("dropped softmax scale", "s[j] = dot * scale;", "s[j] = dot;", 1, 0, ATTN_PINS),
@@ -74,6 +83,16 @@ MUTANTS = [
     ("mean summed in fp32", "acc += (double)scores[i];", "acc = (double)((float)acc + scores[i]);", 1, 0,
      ROUTE_PINS),
     ("mean of +inf and -inf leaves a raw NaN", "if (isnan(qb)) {", "if (0) {", 1, 0, ROUTE_PINS),
+    ("rotation the other way round", "out[e] = bf16_rne(fmaf(re, c, -im_sin));", "out[e] = bf16_rne(fmaf(re, c, im_sin));", 1, 0,
+     ROPE_PINS),
+    ("imaginary part forgets the cosine term", "out[e + 1] = bf16_rne(fmaf(re, sn, im_cos));",
+     "out[e + 1] = bf16_rne(re * sn);", 1, 0, ROPE_PINS),
+    ("pairs taken as first half / second half", "const int64_t e = (t * n_heads + h) * head_dim + 2 * i;\n        const float re = (float)widen(x, e, ORACLE_BF16), im = (float)widen(x, e + 1, ORACLE_BF16);",
+     "const int64_t e = (t * n_heads + h) * head_dim + 2 * i;\n        const float re = (float)widen(x, (t * n_heads + h) * head_dim + i, ORACLE_BF16), im = (float)widen(x, (t * n_heads + h) * head_dim + half + i, ORACLE_BF16);",
+     1, 0, ROPE_PINS),
+    ("angle table indexed by head instead of token", "const float c = cos_t[t * half + i], sn = sin_t[t * half + i];",
+     "const float c = cos_t[(h % n_tokens) * half + i], sn = sin_t[(h % n_tokens) * half + i];", 1, 0, ROPE_PINS),
+    ("bf16 rounding truncates", "u += 0x7FFFu + ((u >> 16) & 1u);", ";", 1, 0, ROPE_PINS),
 ]
 
 
