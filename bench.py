@@ -292,6 +292,20 @@ def main():
                                               "unit": "GB/s", "frac": round(snap_gbps / PEAK_HBM_GBPS, 4),
                                               "bytes": 2.0 * (1 << 30), "ms": round(snap_ms, 4)}
     del snap_src, snap_dst
+    # the commit with the rotary embedding of K fused into the copy (same traffic plus the angle tables)
+    ang = torch.rand((T, 64), device=dev) * 6.283
+    cos_t, sin_t = torch.cos(ang).contiguous(), torch.sin(ang).contiguous()
+
+    def commit_rope():
+        P.kv_commit_rope(cache, k_blk, v_blk, nb, cos_t, sin_t)
+        cache.c.cache_len = c_len                # (timing only: the slot is scrubbed below)
+    cr_ms = time_calls(commit_rope, 5)
+    P.kv_commit_rope(cache, k_blk, v_blk, nb, cos_t, sin_t)
+    P.kv_rollback(cache, c_len)
+    cr_gbps = 2 * payload / (cr_ms * 1e-3) / 1e9
+    line["hbm_kernels"]["kv_commit_rope"] = {"bound": "hbm", "achieved": round(cr_gbps, 1), "peak": PEAK_HBM_GBPS,
+                                             "unit": "GB/s", "frac": round(cr_gbps / PEAK_HBM_GBPS, 4),
+                                             "bytes": 2 * payload, "ms": round(cr_ms, 4)}
 
     # what the matrix cores of this chip deliver with nothing else going on, and at what clock
     P.probe_mfma(4000)

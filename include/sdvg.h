@@ -192,6 +192,35 @@ int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk, i
                    void *stream);
 
 /*
+ * Rotary position embedding of q / k rows (paper Sec. 4.1 "Models": KV caching "via RoPE positional
+ * embeddings"; no formula is printed). Reading taken: elements 2i and 2i+1 of every head's vector
+ * are the real and imaginary part of a complex number that is multiplied by exp(i * angle); the
+ * angle of (token, pair i) is given by the caller as tables, so the position scheme is the
+ * caller's. fp32 arithmetic in a fixed order, bf16 result (RNE):
+ *     re' = fma(re, cos, -(im * sin)),   im' = fma(re, sin, im * cos).
+ *   x, out     device bf16 [n_tokens][n_heads][128] with the given token / head strides
+ *              (elements; multiples of 8, >= 128); out may be x itself (in place), otherwise the
+ *              two must not overlap.
+ *   cos_table, sin_table  device fp32, dense [n_tokens][64], 16-byte aligned.
+ * head_dim must be 128. n_tokens == 0 is a no-op. Asynchronous on `stream`.
+ */
+int sdvg_rope(const void *x, const float *cos_table, const float *sin_table, void *out,
+              int64_t n_tokens, int32_t n_heads, int32_t head_dim, int64_t x_token_stride,
+              int64_t x_head_stride, int64_t out_token_stride, int64_t out_head_stride, void *stream);
+
+/*
+ * sdvg_kv_commit with the rotation of K fused into the copy: k_blk holds the block's keys BEFORE
+ * the rotary embedding; they are rotated (as sdvg_rope, tables [T][64] shared by all layers) on
+ * their way into the cache, v_blk is copied as it is. One pass over the block instead of two,
+ * and the cache holds rotated keys, which is what sdvg_block_attn expects to find there. (Keys
+ * are not rotated "on load" inside the attention kernel: its K tiles go from HBM to LDS without
+ * passing registers, and each of a head's workgroups would rotate every tile again.)
+ * Arguments, rules and errors otherwise as sdvg_kv_commit.
+ */
+int sdvg_kv_commit_rope(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk, int32_t slot,
+                        const float *cos_table, const float *sin_table, void *stream);
+
+/*
  * KV rollback (paper Sec. 3 "Inference flow", reject branch: the target regenerates the block
  * as if the draft had never been in its cache). Sets cache->cache_len = new_len and zero-fills
  * tokens [new_len, old cache_len) of k and v in every layer, so no rejected data survives.

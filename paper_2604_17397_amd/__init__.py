@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     block_attn_workspace_bytes,
     kv_commit,
     kv_rollback,
+    rope,
+    kv_commit_rope,
     buffer_snapshot,
     worst_frame_route,
     worst_frame_route_batch,

@@ -74,6 +74,10 @@ def lib():
         L.sdvg_block_attn_workspace_bytes.argtypes = [ctypes.POINTER(sdvg_attn_desc), i32, i64, i32]
         L.sdvg_kv_commit.restype = ctypes.c_int
         L.sdvg_kv_commit.argtypes = [ctypes.POINTER(sdvg_kv_cache), vp, vp, i32, vp]
+        L.sdvg_rope.restype = ctypes.c_int
+        L.sdvg_rope.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i64, i64, i64, vp]
+        L.sdvg_kv_commit_rope.restype = ctypes.c_int
+        L.sdvg_kv_commit_rope.argtypes = [ctypes.POINTER(sdvg_kv_cache), vp, vp, i32, vp, vp, vp]
         L.sdvg_kv_rollback.restype = ctypes.c_int
         L.sdvg_kv_rollback.argtypes = [ctypes.POINTER(sdvg_kv_cache), i64, vp]
         L.sdvg_worst_frame_route.restype = ctypes.c_int
@@ -295,6 +299,49 @@ def kv_commit(cache, k_blk, v_blk, slot, stream=None):
                               _stream_ptr(stream))
     if st != 0:
         raise SdvgError(st, "sdvg_kv_commit")
+
+
+def _check_tables(cos, sin, n_tokens, device):
+    _check_dev(cos, sin)
+    for t in (cos, sin):
+        if t.dtype != torch.float32 or tuple(t.shape) != (n_tokens, 64) or not t.is_contiguous() or t.device != device:
+            raise ValueError("cos / sin must be dense float32 [tokens, 64] on the tensors' device")
+
+
+def rope(x, cos, sin, out=None, stream=None):
+    """sdvg_rope: rotary embedding of bf16 rows x [tokens, heads, 128] by the angle tables cos, sin
+    float32 [tokens, 64]. out defaults to a new tensor; pass out=x for in place."""
+    _check_dev(x, out)
+    if x.dtype != torch.bfloat16 or x.dim() != 3 or x.shape[2] != 128 or x.stride(2) != 1:
+        raise ValueError("x must be bfloat16 [tokens, heads, 128] with unit dim stride")
+    if out is None:
+        out = torch.empty(x.shape, dtype=x.dtype, device=x.device)
+    elif out.shape != x.shape or out.dtype != x.dtype or out.stride(2) != 1 or out.device != x.device:
+        raise ValueError("out must match x")
+    _check_tables(cos, sin, x.shape[0], x.device)
+    st = lib().sdvg_rope(_ptr(x), _ptr(cos), _ptr(sin), _ptr(out), x.shape[0], x.shape[1], x.shape[2],
+                         x.stride(0), x.stride(1), out.stride(0), out.stride(1), _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_rope")
+    return out
+
+
+def kv_commit_rope(cache, k_blk, v_blk, slot, cos, sin, stream=None):
+    """sdvg_kv_commit_rope: kv_commit with k_blk (dense bf16 [layers, T, heads, 128], BEFORE the
+    rotary embedding) rotated on its way into the cache; cos, sin float32 [T, 64]."""
+    _check_dev(k_blk, v_blk)
+    if not (k_blk.is_contiguous() and v_blk.is_contiguous()):
+        raise ValueError("k_blk and v_blk must be dense")
+    L, T, H, D = cache.c.n_layers, cache.c.block_tokens, cache.c.n_heads, cache.c.head_dim
+    if tuple(k_blk.shape) != (L, T, H, D) or tuple(v_blk.shape) != (L, T, H, D):
+        raise ValueError("block shape must be [layers, T, heads, dim] of the cache")
+    if k_blk.dtype != torch.bfloat16 or v_blk.dtype != torch.bfloat16:
+        raise TypeError("k_blk and v_blk must be bfloat16")
+    _check_tables(cos, sin, T, k_blk.device)
+    st = lib().sdvg_kv_commit_rope(ctypes.byref(cache.c), _ptr(k_blk), _ptr(v_blk), int(slot), _ptr(cos), _ptr(sin),
+                                   _stream_ptr(stream))
+    if st != 0:
+        raise SdvgError(st, "sdvg_kv_commit_rope")
 
 
 def kv_rollback(cache, new_len, stream=None):

@@ -136,17 +136,17 @@ dim3 dense_grid(int64_t chunks_per_layer, int n_layers) {
 
 }  // namespace
 
-extern "C" int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk,
-                              int32_t slot, void *stream) {
+namespace sdvg {
+// Host-side checks shared by every commit entry point: descriptor, pointers, the append-only slot
+// rule, and that the source does not alias the slot it is copied into (in any layer).
+int check_commit_args(const sdvg_kv_cache *cache, const void *k_blk, const void *v_blk, int32_t slot) {
   int st = validate_cache(cache);
   if (st != SDVG_OK) return st;
   if (!k_blk || !v_blk) return SDVG_ERR_NULL;
-  if (!sdvg::aligned16(k_blk) || !sdvg::aligned16(v_blk)) return SDVG_ERR_ALIGN;
+  if (!aligned16(k_blk) || !aligned16(v_blk)) return SDVG_ERR_ALIGN;
   const int64_t T = cache->block_tokens;
   if (slot < 0 || slot * T != cache->cache_len || (slot + 1) * T > cache->capacity_tokens)
     return SDVG_ERR_RANGE;
-  // The source must not alias the slot it is copied into (in any layer): the copy kernels read
-  // and write in no particular order.
   const int64_t src_bytes = static_cast<int64_t>(cache->n_layers) * T * cache->n_heads * 128 * 2;
   const int64_t dst_bytes = token_range_span(cache, T) * 2;
   for (int l = 0; l < cache->n_layers; ++l) {
@@ -156,6 +156,15 @@ extern "C" int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const voi
       if (ranges_overlap(src, src_bytes, dk, dst_bytes) || ranges_overlap(src, src_bytes, dv, dst_bytes))
         return SDVG_ERR_RANGE;
   }
+  return SDVG_OK;
+}
+}  // namespace sdvg
+
+extern "C" int sdvg_kv_commit(sdvg_kv_cache *cache, const void *k_blk, const void *v_blk,
+                              int32_t slot, void *stream) {
+  int st = sdvg::check_commit_args(cache, k_blk, v_blk, slot);
+  if (st != SDVG_OK) return st;
+  const int64_t T = cache->block_tokens;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t chunks_per_layer = T * cache->n_heads * 16;
   if (dense_token_major(cache)) {

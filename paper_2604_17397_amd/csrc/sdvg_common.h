@@ -17,6 +17,9 @@ inline int device_error(hipError_t e) {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// kv_cache.hip: host-side checks shared by every commit entry point.
+int check_commit_args(const sdvg_kv_cache *cache, const void *k_blk, const void *v_blk, int32_t slot);
+
 }  // namespace sdvg
 
 #define SDVG_HIP_CHECK(expr)                                   \

@@ -203,6 +203,58 @@ def test_binding_checks_shapes_before_the_call(P, monkeypatch):
             b.block_attn(**args)
 
 
+def test_rope_rejects_bad_arguments(P):
+    f = P.lib().sdvg_rope
+    ok = dict(x=FAKE, c=FAKE, s=FAKE, out=FAKE, n=4, H=2, d=128, xts=256, xhs=128, ots=256, ohs=128)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return f(a["x"], a["c"], a["s"], a["out"], a["n"], a["H"], a["d"], a["xts"], a["xhs"], a["ots"], a["ohs"], None)
+    assert call(n=0) == 0                       # nothing to do
+    assert call(n=-1) == -2 and call(H=0) == -2
+    assert call(d=64) == -5
+    assert call(x=None) == -1 and call(c=None) == -1 and call(out=None) == -1
+    assert call(xts=100) == -2 and call(ohs=132) == -4
+    assert call(x=FAKE + 2) == -4 and call(s=FAKE + 4) == -4
+    g = P.lib().sdvg_kv_commit_rope
+    c = make_cache(P)
+    assert g(ctypes.byref(c), FAKE, FAKE, 1, None, FAKE, None) == -1
+    assert g(ctypes.byref(c), FAKE, FAKE, 1, FAKE + 4, FAKE, None) == -4
+    assert g(ctypes.byref(c), FAKE, FAKE, 0, FAKE, FAKE, None) == -3      # slot already filled
+    assert g(ctypes.byref(c), None, FAKE, 1, FAKE, FAKE, None) == -1
+    assert c.cache_len == 4
+
+
+def test_fused_commit_rejects_bad_arguments(P):
+    d = make_desc(P)
+    f = P.lib().sdvg_block_attn_commit
+    assert f(ctypes.byref(d), FAKE, None, FAKE, FAKE, FAKE, 0, FAKE, None) == -1       # needs the cache
+    d.dtype = 1
+    assert f(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None) == -5       # bf16 only
+    d = make_desc(P, kv_token_stride=260)
+    assert f(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None) == -4
+    c = make_cache(P)
+    assert P.lib().sdvg_kv_commit_mark(ctypes.byref(c), 0) == -3 and c.cache_len == 4
+    assert P.lib().sdvg_kv_commit_mark(ctypes.byref(c), 1) == 0 and c.cache_len == 8
+
+
+def test_batch_rejects_bad_arguments(P):
+    d = make_desc(P)
+    arr = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    f = P.lib().sdvg_block_attn_batch
+    assert f(ctypes.byref(d), 0, arr, arr, arr, arr, arr, 0, arr, None, 0, 0, None) == -2
+    assert f(ctypes.byref(d), 9, arr, arr, arr, arr, arr, 0, arr, None, 0, 0, None) == -2
+    assert f(ctypes.byref(d), 2, arr, arr, arr, arr, arr, 0, arr, None, -1, 0, None) == -2
+    assert f(ctypes.byref(d), 2, arr, arr, arr, arr, arr, 0, arr, None, 0, 7, None) == -5
+    assert f(ctypes.byref(d), 2, None, arr, arr, arr, arr, 0, arr, None, 0, 0, None) == -1
+    bad = (ctypes.c_void_p * 2)(FAKE, None)
+    assert f(ctypes.byref(d), 2, bad, arr, arr, arr, arr, 0, arr, None, 0, 0, None) == -1
+    assert P.lib().sdvg_block_attn_workspace_bytes(ctypes.byref(d), 0, 0, 1) == -2
+    assert P.lib().sdvg_block_attn_workspace_bytes(ctypes.byref(d), 1, 0, 9) == -5
+    assert P.lib().sdvg_block_attn_static_workspace_limit() == 64 << 20
+
+
 def test_missing_library_fails_loudly(P, monkeypatch):
     import paper_2604_17397_amd.binding as b
     monkeypatch.setattr(b, "_LIB", None)
