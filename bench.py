@@ -307,19 +307,25 @@ def main():
                                              "unit": "GB/s", "frac": round(cr_gbps / PEAK_HBM_GBPS, 4),
                                              "bytes": 2 * payload, "ms": round(cr_ms, 4)}
 
-    # what the matrix cores of this chip deliver with nothing else going on, and at what clock
-    P.probe_mfma(4000)
-    torch.cuda.synchronize()
-    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    pe[0].record()
-    probe_flops, probe_cycles = P.probe_mfma(40000)
-    pe[1].record()
-    torch.cuda.synchronize()
-    probe_ms = pe[0].elapsed_time(pe[1])
-    line["roofline"]["mfma_only_probe"] = {
-        "tflops": round(probe_flops / (probe_ms * 1e-3) / 1e12, 1),
-        "clock_ghz": round(int(probe_cycles.item()) / (probe_ms * 1e-3) / 1e9, 3),
-        "note": "register-only bf16 MFMA loop on the same chip; the 2500 peak assumes 2.4 GHz"}
+    # what the matrix cores of this chip deliver with nothing else going on, and at what clock:
+    # with two operand registers that never change, and with operands that change as a kernel's do
+    def probe(changing):
+        P.probe_mfma(4000, changing=changing)
+        torch.cuda.synchronize()
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        pe[0].record()
+        probe_flops, probe_cycles = P.probe_mfma(40000, changing=changing)
+        pe[1].record()
+        torch.cuda.synchronize()
+        probe_ms = pe[0].elapsed_time(pe[1])
+        return {"tflops": round(probe_flops / (probe_ms * 1e-3) / 1e12, 1),
+                "clock_ghz": round(int(probe_cycles.item()) / (probe_ms * 1e-3) / 1e9, 3)}
+    line["roofline"]["mfma_only_probe"] = dict(
+        probe(False), note="register-only bf16 MFMA loop on the same chip, constant operands; "
+                           "the 2500 peak assumes 2.4 GHz")
+    line["roofline"]["mfma_only_probe_changing_operands"] = dict(
+        probe(True), note="the same loop with a different random A operand for every MFMA and a "
+                          "different B operand every second one, as in the attention kernel")
 
     parity_ok = True
     if not args.no_cpu_baseline:

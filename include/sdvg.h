@@ -298,6 +298,17 @@ int sdvg_avg_frame_route_batch(const float *frame_scores, int32_t n_blocks, int3
 int sdvg_probe_mfma(float *out, int64_t n_out, uint64_t *cycles, int32_t iters, double *flops_out,
                     void *stream);
 
+/*
+ * The same measurement with operands that change: the A operand of every MFMA differs from the
+ * previous one's and the B operand changes every second MFMA (register sets filled with random
+ * signs and mantissas, magnitudes 1/8 .. 4), as the operands of an attention kernel do. The
+ * chip holds a lower clock under this load than under sdvg_probe_mfma's, whose two operand
+ * registers never change; this is the rate to compare a real kernel with.
+ * Arguments, return values and FLOP count as for sdvg_probe_mfma.
+ */
+int sdvg_probe_mfma_changing(float *out, int64_t n_out, uint64_t *cycles, int32_t iters,
+                             double *flops_out, void *stream);
+
 /* Human-readable name of a status code (static storage; never NULL). */
 const char *sdvg_status_string(int status);
 

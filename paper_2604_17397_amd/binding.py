@@ -92,6 +92,8 @@ def lib():
         L.sdvg_avg_frame_route_batch.argtypes = [vp, i32, i32, f32, vp, i32, vp, vp, vp]
         L.sdvg_probe_mfma.restype = ctypes.c_int
         L.sdvg_probe_mfma.argtypes = [vp, i64, vp, i32, ctypes.POINTER(ctypes.c_double), vp]
+        L.sdvg_probe_mfma_changing.restype = ctypes.c_int
+        L.sdvg_probe_mfma_changing.argtypes = [vp, i64, vp, i32, ctypes.POINTER(ctypes.c_double), vp]
         L.sdvg_status_string.restype = ctypes.c_char_p
         L.sdvg_status_string.argtypes = [ctypes.c_int]
         L.sdvg_last_device_error.restype = ctypes.c_int
@@ -401,15 +403,17 @@ def worst_frame_route_batch(frame_scores, tau, block_idx=None, first_block_idx=0
     return dec, qb
 
 
-def probe_mfma(iters=20000, stream=None):
-    """sdvg_probe_mfma: enqueues the MFMA-only measurement kernel. Returns (flops, cycles) with
-    cycles a device uint64 tensor (as int64) holding wave 0's shader clocks once it has run."""
+def probe_mfma(iters=20000, stream=None, changing=False):
+    """sdvg_probe_mfma (or, with changing=True, sdvg_probe_mfma_changing): enqueues the MFMA-only
+    measurement kernel. Returns (flops, cycles) with cycles a device uint64 tensor (as int64)
+    holding wave 0's shader clocks once it has run."""
     dev = torch.device("cuda", torch.cuda.current_device())
     out = torch.empty(256 * 256, dtype=torch.float32, device=dev)
     cycles = torch.zeros(1, dtype=torch.int64, device=dev)
     flops = ctypes.c_double(0.0)
-    st = lib().sdvg_probe_mfma(_ptr(out), out.numel(), _ptr(cycles), int(iters), ctypes.byref(flops),
-                               _stream_ptr(stream))
+    name = "sdvg_probe_mfma_changing" if changing else "sdvg_probe_mfma"
+    st = getattr(lib(), name)(_ptr(out), out.numel(), _ptr(cycles), int(iters), ctypes.byref(flops),
+                              _stream_ptr(stream))
     if st != 0:
-        raise SdvgError(st, "sdvg_probe_mfma")
+        raise SdvgError(st, name)
     return flops.value, cycles

@@ -326,7 +326,6 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
   auto wait_lds = [&](auto n_c) __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0xC07F | (decltype(n_c)::value << 8));
   };
-  using N0 = std::integral_constant<int, 0>;
   using N2 = std::integral_constant<int, 2>;
   using N4 = std::integral_constant<int, 4>;
   // QK group g; K group g+1 (or, after the last group, V group 0 of slot vslot) goes into `nxt`.
@@ -366,24 +365,19 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     mfma_k(cur[3], 2 * g + 1, 1);
     SDVG_SB();
   };
-  // PV group j with the V^T operands of step j+1 fetched into `nxt` (none after j = 3).
+  // PV group j (0..2) with the V^T operands of step j+1 fetched into `nxt`; the last group is
+  // written out in tile_body.
   auto pv_group = [&](const bf16x8(&cur)[4], bf16x8(&nxt)[4], int slot, int j)
       __attribute__((always_inline)) {
     SDVG_SB();
-    if (j < 3) {
-      read_v(nxt[0], slot, j + 1, 0);
-      read_v(nxt[1], slot, j + 1, 1);
-      wait_lds(N4{});
-    } else {
-      wait_lds(N0{});
-    }
+    read_v(nxt[0], slot, j + 1, 0);
+    read_v(nxt[1], slot, j + 1, 1);
+    wait_lds(N4{});
     SDVG_SB();
     mfma_v(cur[0], j, 0);
     SDVG_SB();
-    if (j < 3) {
-      read_v(nxt[2], slot, j + 1, 2);
-      read_v(nxt[3], slot, j + 1, 3);
-    }
+    read_v(nxt[2], slot, j + 1, 2);
+    read_v(nxt[3], slot, j + 1, 3);
     SDVG_SB();
     mfma_v(cur[1], j, 1);
     mfma_v(cur[2], j, 2);
@@ -535,11 +529,23 @@ __global__ __launch_bounds__(512) void block_attn_bf16_kernel(const AttnParams p
     pv_group(fa, fb, R, 0);
     pv_group(fb, fa, R, 1);
     pv_group(fa, fb, R, 2);
-    pv_group(fb, fa, R, 3);
-    // let this wave's last MFMAs retire before the partner wave takes over the matrix pipe
-    asm volatile("" : "+v"(o_acc[0]), "+v"(o_acc[1]), "+v"(o_acc[2]), "+v"(o_acc[3]));
-    __builtin_amdgcn_s_setprio(0);
+    // Last PV group with the barrier ahead of its last MFMA. Everything this phase reads from LDS
+    // has landed by then (the wait below), which is all the barrier stands for on this side;
+    // the MFMA left over works on registers only and runs, at raised priority, while the partner
+    // wave wakes up and gets its first operands ready, so the matrix pipe has work across the
+    // hand-over. (More than one MFMA behind the barrier makes the vector phase the longer one.)
+    SDVG_SB();
+    wait_lds0();
+    mfma_v(fb[0], 3, 0);
+    mfma_v(fb[1], 3, 1);
+    mfma_v(fb[2], 3, 2);
+    SDVG_SB();
+    __builtin_amdgcn_s_setprio(2);
     wg_barrier();
+    SDVG_SB();
+    mfma_v(fb[3], 3, 3);
+    SDVG_SB();
+    __builtin_amdgcn_s_setprio(0);
   };
   // ---- prologue: the piece's first three tiles into ring slots 0..2, then S of the first
 #pragma unroll
