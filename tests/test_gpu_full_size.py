@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+"""GPU parity at the full benchmark sizes (14B target shape), in the launch configuration bench.py times.
 
 The oracle cannot run the whole problem (3.1 TFLOP-equivalent per call in fp64), so attention is
 checked on sampled query rows -- rows are independent, so the sampled rows are checked exactly
