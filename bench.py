@@ -307,6 +307,16 @@ def main():
                                              "unit": "GB/s", "frac": round(cr_gbps / PEAK_HBM_GBPS, 4),
                                              "bytes": 2 * payload, "ms": round(cr_ms, 4)}
 
+    # the rotary embedding alone, on one layer's q (what a step pays for q and for the block's own K)
+    rope_out = torch.empty_like(q)
+    rope_ms = time_calls(lambda: P.rope(q, cos_t, sin_t, out=rope_out), 20)
+    rope_bytes = 2.0 * q.numel() * 2
+    line["hbm_kernels"]["rope_one_layer_q"] = {"bound": "hbm", "achieved": round(rope_bytes / (rope_ms * 1e-3) / 1e9, 1),
+                                               "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                               "frac": round(rope_bytes / (rope_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                                               "bytes": rope_bytes, "ms": round(rope_ms, 4)}
+    del rope_out
+
     # what the matrix cores of this chip deliver with nothing else going on, and at what clock:
     # with two operand registers that never change, and with operands that change as a kernel's do
     def probe(changing):

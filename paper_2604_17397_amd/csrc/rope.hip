@@ -11,7 +11,7 @@
 // go from HBM to LDS without passing through registers, and every one of a head's 19 workgroups
 // would have to rotate every tile again. Rotating once, in the bandwidth-bound copy that commits
 // the block, costs nothing; q and the current block's K are rotated by the plain kernel (one
-// pass over 2 x 48 MB per layer at the target shape, ~15 us against 2.4 ms of attention).
+// pass over 48 MB in and out per tensor and layer at the target shape, 17 us against 2.4 ms of attention).
 #include "sdvg_common.h"
 
 namespace {

@@ -161,3 +161,20 @@ def test_head_major_strides():
     torch.cuda.synchronize()
     ref = oracle.block_attn(q, kc, vc, kb, vb, c_len)
     check(attn_errors(bits_of(out), ref))
+
+
+def test_random_small_shapes():
+    """Thirty seeded draws of (heads, cache_len, n_blk, n_q, jitter, spare cache rows): every row of
+    every draw against the oracle. The draws cover several tiles, the seam inside a tile, ragged
+    tails, a single key and more query rows than one workgroup holds."""
+    rng = np.random.default_rng(20260417)
+    for case in range(30):
+        H = int(rng.integers(1, 6))
+        cache_len = int(rng.choice([0, int(rng.integers(1, 64)), int(rng.integers(64, 400))]))
+        n_blk = int(rng.integers(1, 330))
+        n_q = int(rng.integers(1, n_blk + 1))
+        jitter = bool(rng.integers(0, 2))
+        errs = run_case(H, n_blk, cache_len, seed=5000 + case, jitter=jitter, cap_extra=int(rng.integers(0, 5)), n_q=n_q)
+        max_abs, rel_rms = errs
+        assert np.isfinite(max_abs) and max_abs <= BF16_MAX_ABS and rel_rms <= BF16_REL_RMS, \
+            (case, H, cache_len, n_blk, n_q, jitter, errs)
