@@ -410,6 +410,7 @@ def cpu_baseline(np, torch, si, cache, q, k_blk, v_blk, c_len, out, P):
             "host_logical_cpus": os.cpu_count(), "kind": "oracle", "seconds": round(dt, 2),
             "sample": "%d of %d query rows x all %d heads of layer 0, all %d keys (fp64, OpenMP)"
                       % (len(rows), n_q, H, n_k),
+            "extrapolated_seconds_for_one_full_call": round(dt * n_q / len(rows), 1),
             "gpu_vs_oracle_on_sample": {"max_abs_err": float(np.max(np.abs(err))),
                                         "rel_rms": float(math.sqrt(num.sum() / den.sum())),
                                         "worst_head_rel_rms": float(per_head.max()),
