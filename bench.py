@@ -242,6 +242,29 @@ def main():
                                              "commit_hidden_ms": round(ms_sep - ms_fus, 3)}
         P.kv_rollback(cache, c_len)              # scrub the slot the fused launches filled
 
+        # -- speculative rounds by threshold (optimistic mode: the draft's K/V are staged in the slot, the
+        #    router decides, a reject scrubs the slot). 64 seeded rounds per tau, correlated frame scores.
+        def rounds(tau_, n=64):
+            sc = torch.from_numpy(si.frame_scores_correlated(si.SEED + 7, n)).to(dev)
+            ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n)]
+            acc = 0
+            for i in range(n):
+                ev[i][0].record()
+                P.kv_commit(cache, k_blk, v_blk, nb)
+                ev[i][1].record()
+                dec_, _ = P.worst_frame_route(sc[i], tau_, nb)
+                ev[i][2].record()
+                P.kv_rollback(cache, c_len)      # on accept too: every round starts from the same cache
+                ev[i][3].record()
+                acc += int(dec_)
+            torch.cuda.synchronize()
+            c_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / n
+            return {"rounds": n, "accepted": acc,
+                    "commit_gbps": round(2 * payload / (c_ms * 1e-3) / 1e9, 1),
+                    "route_us": round(sum(e[1].elapsed_time(e[2]) for e in ev) / n * 1e3, 1),
+                    "rollback_gbps": round(payload / (sum(e[2].elapsed_time(e[3]) for e in ev) / n * 1e-3) / 1e9, 1)}
+        other["speculative_rounds_by_tau"] = {str(t_): rounds(t_) for t_ in (-1.0, -0.7, -0.4)}
+
         # -- 7-block streaming generation, attention only: block k = 0..6 runs S x L calls at cache_len 4680 k
         def streaming(Ls, Hs, kk, vv, kb_, vb_, qq, oo):
             fl, ms_tot = 0.0, 0.0
